@@ -1,0 +1,162 @@
+"""Pins for the oracle's fused reorder, per-cluster quantization, weight
+quantization and the two forms of the cluster-wise product."""
+import numpy as np
+import pytest
+
+import workloads as w
+from oracle import rptq_oracle as o
+
+
+def _setup(seed=21, d=48, M=12, g=4, bits=4, N=10):
+    s = w.tiny_site(seed, d, M, n_cal=3, cal_rows=24)
+    cal = o.calibrate(s.cal, s.gamma, s.beta, 1e-5, False, g, bits, seed=seed)
+    W = w.weight_matrix(seed + 1, N, d)
+    return s, cal, W
+
+
+@pytest.mark.parametrize("bits", [3, 4, 8])
+def test_fused_reorder_equals_explicit_permute_then_quantize(bits):
+    s, cal, _ = _setup(bits=bits)
+    codes, xsum, fr = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off,
+                                 cal.inv_s, cal.z, bits)
+    # explicit: LN in original order, physically permute, quantize cluster by cluster
+    y, _ = o.layernorm_f32(s.x, s.gamma, s.beta, 1e-5)
+    yt = y[:, cal.perm]
+    for i in range(cal.g_eff):
+        a, b = cal.cluster_off[i], cal.cluster_off[i + 1]
+        ref = o.quantize(yt[:, a:b], cal.inv_s[i], cal.z[i], bits)
+        assert np.array_equal(codes[:, a:b], ref)
+        assert np.array_equal(xsum[:, i], ref.sum(axis=1))
+    # fused: gamma/beta gathered, LN run on the reordered row
+    gr, br = o.fold_layernorm(s.gamma, s.beta, cal.perm)
+    yf, fr2 = o.layernorm_f32(s.x[:, cal.perm], gr, br, 1e-5)
+    ok = ~(fr | fr2)
+    sizes = np.diff(cal.cluster_off)
+    cf = o.quantize(yf, np.repeat(cal.inv_s, sizes)[None], np.repeat(cal.z, sizes)[None], bits)
+    assert ok.sum() >= ok.size - 1
+    assert np.array_equal(cf[ok], codes[ok])
+
+
+def test_one_cluster_is_per_tensor_and_c_clusters_is_per_channel():
+    s, _, _ = _setup()
+    bits = 4
+    cmin, cmax = o.calibrate_minmax(s.cal, s.gamma, s.beta, 1e-5)
+    y, _ = o.layernorm_f32(s.x, s.gamma, s.beta, 1e-5)
+    # g = 1
+    cal1 = o.calibrate(s.cal, s.gamma, s.beta, 1e-5, False, 1, bits)
+    assert cal1.g_eff == 1 and np.array_equal(cal1.perm, np.arange(s.d))
+    c1, _, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal1.perm, cal1.cluster_off, cal1.inv_s, cal1.z, bits)
+    st, invt, zt = o.minmax_params(cmin.min(), cmax.max(), bits)
+    assert np.array_equal(c1, o.quantize(y, invt, zt, bits))
+    # g = C (distinct points): every channel its own cluster
+    calC = o.calibrate(s.cal, s.gamma, s.beta, 1e-5, False, s.d, bits)
+    assert calC.g_eff == s.d
+    cC, _, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, calC.perm, calC.cluster_off, calC.inv_s, calC.z, bits)
+    sc, invc, zc = o.minmax_params(cmin, cmax, bits)
+    ref = o.quantize(y, invc[None], zc[None], bits)
+    assert np.array_equal(cC, ref[:, calC.perm])
+
+
+def test_calibration_outputs_are_a_partition():
+    s, cal, _ = _setup(g=5)
+    assert sorted(cal.perm.tolist()) == list(range(s.d))
+    assert cal.cluster_off[0] == 0 and cal.cluster_off[-1] == s.d
+    assert (np.diff(cal.cluster_off) > 0).all()
+    assert cal.assign[0] == 0
+    for i in range(cal.g_eff):
+        mem = cal.perm[cal.cluster_off[i]:cal.cluster_off[i + 1]]
+        assert (cal.assign[mem] == i).all() and (np.diff(mem) > 0).all()
+    # calibration rows never clamp by more than the top-code cut of Eq. 2
+    for xb in s.cal:
+        codes, _, _ = o.ln_quant(xb, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off, cal.inv_s, cal.z, 4)
+        assert codes.min() >= -8 and codes.max() <= 7
+
+
+def test_weight_quantization_per_output_channel():
+    s, cal, W = _setup()
+    wq, sW, invW, zW = o.quantize_weights(W, cal.perm)
+    assert wq.min() >= -8 and wq.max() <= 7
+    for r in range(W.shape[0]):                              # Eq. 2 / Eq. 1 row by row
+        sr, invr, zr = o.minmax_params(W[r].min(), W[r].max(), 4)
+        assert float(sr) == float(sW[r]) and int(zr) == int(zW[r])
+        assert np.array_equal(wq[r], o.quantize(W[r][cal.perm], invr, zr, 4))
+    # column reorder commutes with per-row quantization; row reorder permutes rows
+    wq0, _, _, _ = o.quantize_weights(W, np.arange(s.d))
+    assert np.array_equal(wq, wq0[:, cal.perm])
+    po = np.random.default_rng(0).permutation(W.shape[0])
+    wq2, sW2, _, zW2 = o.quantize_weights(W, cal.perm, po)
+    assert np.array_equal(wq2, wq[po]) and np.array_equal(sW2, sW[po]) and np.array_equal(zW2, zW[po])
+    # a row's extremes land on the extreme codes (within the 2^k divisor cut)
+    assert (wq.min(axis=1) == -8).all() and (wq.max(axis=1) >= 6).all()
+
+
+def _brute_force_gemm(xq, wq, off, sX, zX, sW, zW):
+    g = len(off) - 1
+    M, N = xq.shape[0], wq.shape[0]
+    Yq = [[[0] * N for _ in range(M)] for _ in range(g)]
+    Y = np.zeros((M, N))
+    for t in range(M):
+        for n in range(N):
+            acc = 0.0
+            for i in range(g):
+                tot = 0
+                for c in range(int(off[i]), int(off[i + 1])):
+                    tot += (int(xq[t, c]) - int(zX[i])) * (int(wq[n, c]) - int(zW[n]))
+                Yq[i][t][n] = tot
+                acc += float(sX[i]) * float(sW[n]) * tot
+            Y[t, n] = acc
+    return np.array(Yq, dtype=np.int64), Y
+
+
+@pytest.mark.parametrize("bits", [3, 4, 8])
+def test_integer_form_against_brute_force_and_dequantized_form(bits):
+    s, cal, W = _setup(bits=bits)
+    codes, xsum, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off, cal.inv_s, cal.z, bits)
+    wq, sW, _, zW = o.quantize_weights(W, cal.perm)
+    P, Yq, Y = o.cluster_gemm_int(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    Yq_ref, Y_ref = _brute_force_gemm(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    assert np.array_equal(Yq, Yq_ref)
+    scale = np.abs(Y_ref).max()
+    assert np.abs(Y - Y_ref).max() <= 1e-12 * scale
+    Y1 = o.cluster_gemm_dequant(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)   # method 1
+    assert np.abs(Y - Y1).max() <= 1e-12 * scale
+    # raw products are the plain integer matrix product of each cluster's slice
+    for i in range(cal.g_eff):
+        a, b = cal.cluster_off[i], cal.cluster_off[i + 1]
+        assert np.array_equal(P[i], codes[:, a:b].astype(np.int64) @ wq[:, a:b].astype(np.int64).T)
+
+
+def test_product_invariant_to_order_inside_clusters_and_cluster_relabelling():
+    s, cal, W = _setup(g=3)
+    bits = 4
+    codes, _, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off, cal.inv_s, cal.z, bits)
+    wq, sW, _, zW = o.quantize_weights(W, cal.perm)
+    _, _, Y = o.cluster_gemm_int(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    rng = np.random.default_rng(1)
+    shuffle = np.concatenate([cal.cluster_off[i] + rng.permutation(cal.cluster_off[i + 1] - cal.cluster_off[i])
+                              for i in range(cal.g_eff)])
+    _, _, Y2 = o.cluster_gemm_int(codes[:, shuffle], wq[:, shuffle], cal.cluster_off, cal.s, cal.z, sW, zW)
+    assert np.abs(Y - Y2).max() <= 1e-12 * np.abs(Y).max()
+    # swap the first two clusters wholesale
+    a, b, c = cal.cluster_off[0], cal.cluster_off[1], cal.cluster_off[2]
+    order = np.concatenate([np.arange(b, c), np.arange(a, b), np.arange(c, s.d)])
+    off2 = np.array([0, c - b, c - a + 0, s.d])
+    sw = [1, 0, 2]
+    _, _, Y3 = o.cluster_gemm_int(codes[:, order], wq[:, order], off2, cal.s[sw], cal.z[sw], sW, zW)
+    assert np.abs(Y - Y3).max() <= 1e-12 * np.abs(Y).max()
+
+
+def test_quantized_product_approximates_the_float_layer():
+    """End to end: the A8 path tracks the unquantized LayerNorm + linear layer, and
+    clustering helps (more clusters, lower error) on the outlier-channel inputs."""
+    s = w.tiny_site(31, 256, 64, n_cal=4, cal_rows=64)
+    W = w.weight_matrix(32, 40, 256)
+    y, _ = o.layernorm_f32(s.x, s.gamma, s.beta, 1e-5)
+    errs = []
+    for g in (1, 8):
+        cal = o.calibrate(s.cal, s.gamma, s.beta, 1e-5, False, g, 4, seed=1)
+        codes, _, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off, cal.inv_s, cal.z, 4)
+        sizes = np.diff(cal.cluster_off)
+        xh = o.dequantize(codes, np.repeat(cal.s, sizes)[None], np.repeat(cal.z, sizes)[None])
+        errs.append(np.linalg.norm(xh - y[:, cal.perm]) / np.linalg.norm(y))
+    assert errs[1] < 0.5 * errs[0]
