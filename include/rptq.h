@@ -1,0 +1,218 @@
+/*
+ * rptq.h - C ABI of the MI355X (gfx950) implementation of the RPTQ inference hot path
+ * (reorder-based post-training quantization, arXiv 2304.01089).
+ *
+ * The path: a LayerNorm whose output leaves the kernel already in cluster order
+ * (Sec. 4.2, "Avoid explicit reordering"), asymmetric round-to-nearest activation
+ * quantization with one (scale, zero point) per channel cluster (Eq. 1, Eq. 2,
+ * Sec. 4.1), and the integer-domain cluster-wise product of App. A.4 against 4-bit
+ * per-output-channel weights whose input columns were permuted offline (Sec. 4.2).
+ *
+ * Conventions
+ *  - Every function returns an rptq_status (0 = RPTQ_OK, negative = error).  Arguments
+ *    are validated on the host before any HIP call; a failed validation launches nothing.
+ *  - The caller owns all memory.  "device" pointers are HIP device memory, 16-byte
+ *    aligned; "host" pointers are ordinary host memory.  Except for rptq_calibrate's
+ *    own use of its workspace the library keeps no state between calls.
+ *  - `stream` is a hipStream_t passed as void*.  Calls are asynchronous on that stream
+ *    unless the description says the call synchronizes.
+ *  - Cluster tables (cluster_off, scales, zero points) are small host arrays with
+ *    1 <= g <= RPTQ_MAX_CLUSTERS; they travel to the kernels by value.
+ *  - bf16 is the upper half of an IEEE fp32.
+ *
+ * Padded cluster-order layout ("K_p")
+ *    Cluster i with n_i = cluster_off[i+1]-cluster_off[i] channels occupies
+ *    pad32(n_i) consecutive positions; the total is rounded up to a multiple of
+ *    RPTQ_K_ALIGN (128).  Pad positions hold activation code 0 and weight code 0 and
+ *    never contribute.  rptq_padded_k() returns K_p.
+ *
+ * Packed activation codes: row-major, one row = K_p/32 groups of 32 codes.
+ *    8 bit : 32 bytes, code j in byte j (two's complement).
+ *    4 bit : 16 bytes = 4 dwords; byte b of dword u = (c[8u+b] << 4) | (c[8u+4+b] & 15).
+ *    3 bit : 12 bytes = dwords x0,x1,x2 with f = c & 7:
+ *            x0.byte b = f[b]<<5    | f[4+b]<<2  | f[24+b]>>1
+ *            x1.byte b = f[8+b]<<5  | f[12+b]<<2 | f[28+b]>>1
+ *            x2.byte b = f[16+b]<<5 | f[20+b]<<2 | (f[28+b]&1)<<1 | (f[24+b]&1)
+ *    (each field sits where one shift and one mask turn it into a sign-carrying int8
+ *    lane of an MFMA operand: 3-bit codes are stored packed and computed as 8-bit,
+ *    as App. A.4 says such values must be cast to a supported width).
+ *
+ * Packed weights: N_p = N rounded up to 256 rows, in blocks of 32 rows x 32 columns
+ *    of K_p; block (rb, s) starts at byte ((rb * K_p/32) + s) * 512 and holds 64 slots
+ *    of 8 bytes; slot h*32 + r (h = 0,1) carries row rb*32+r, columns s*32 + h*16 .. +15
+ *    as two 4-bit dwords in the 4-bit code format above.
+ */
+#ifndef RPTQ_H
+#define RPTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RPTQ_MAX_CLUSTERS 64
+#define RPTQ_K_ALIGN 128
+#define RPTQ_N_ALIGN 256
+#define RPTQ_MAX_CHANNELS 32768
+
+typedef enum {
+  RPTQ_OK = 0,
+  RPTQ_ERR_NULL = -1,      /* a required pointer is NULL */
+  RPTQ_ERR_SHAPE = -2,     /* a size is out of range or inconsistent */
+  RPTQ_ERR_BITS = -3,      /* activation bits not in {3,4,8} */
+  RPTQ_ERR_ALIGN = -4,     /* a device pointer is not 16-byte aligned */
+  RPTQ_ERR_PERM = -5,      /* perm is not a permutation / cluster_off not increasing */
+  RPTQ_ERR_RANGE = -6,     /* a zero point or scale is outside what the kernels carry exactly */
+  RPTQ_ERR_WORKSPACE = -7, /* workspace too small */
+  RPTQ_ERR_HIP = -8        /* a HIP call failed; see rptq_last_hip_error() */
+} rptq_status;
+
+enum { RPTQ_DTYPE_BF16 = 0, RPTQ_DTYPE_F32 = 1 };
+
+/* ---- sizes (host only, no HIP call) ------------------------------------------- */
+
+/* K_p of the padded cluster-order layout.  cluster_off: host [g+1], strictly increasing from 0. */
+int32_t rptq_padded_k(const int32_t* cluster_off, int32_t g, int32_t* k_padded);
+/* Bytes of a packed activation-code buffer of M rows (0 on bad arguments). */
+size_t rptq_codes_bytes(int64_t M, int32_t k_padded, int32_t bits);
+/* Bytes of a packed weight buffer for N output channels (0 on bad arguments). */
+size_t rptq_weight_bytes(int32_t N, int32_t k_padded);
+/* Device workspace rptq_calibrate needs for d channels. */
+size_t rptq_calibrate_workspace_bytes(int32_t d);
+
+/* ---- calibration: Sec. 4.1 ------------------------------------------------------
+ * Per-channel minimum and maximum of the site's activation over all calibration rows
+ * (first displayed equation of Sec. 4.1), K-Means over the points (min_c, max_c) into g
+ * clusters, the reorder index S = [S^1..S^g], and one Min-Max (Eq. 2) parameter pair per
+ * cluster.  The activation is LayerNorm(x) when gamma/beta are given (biased variance,
+ * statistics in fp64, elementwise chain in fp32), else x, with max(.,0) applied when
+ * relu != 0.
+ *
+ * K-Means rule (the paper names the algorithm only): Euclidean distance on raw fp32
+ * (min,max) points held as fp64; D^2-weighted seeding driven by SplitMix64(seed); Lloyd
+ * iterations until the assignment repeats or max_iter; ties to the lowest cluster id;
+ * an empty cluster is re-seeded with the point farthest from its own centre; clusters
+ * are renumbered by first occurrence and members keep ascending channel order.
+ *
+ *  x_batches  host array [n_batches] of device bf16 [rows[b], d] row-major
+ *  gamma,beta device fp32 [d], both NULL for a non-LayerNorm site
+ *  ch_min/max host fp32 [d] out;  assign host int32 [d] out (cluster of each channel)
+ *  perm       host int32 [d] out: reordered column j is original channel perm[j]
+ *  cluster_off host int32 [g+1] out; s, inv_s host fp32 [g] out; z host int32 [g] out
+ *  g_eff      host out: clusters actually produced (<= g when points coincide); entries
+ *             beyond g_eff are not written
+ *  workspace  device, rptq_calibrate_workspace_bytes(d)
+ * Synchronizes the stream before returning.  RPTQ_ERR_RANGE if a zero point exceeds 2^21.
+ */
+int32_t rptq_calibrate(const void* const* x_batches, const int64_t* rows, int32_t n_batches, int32_t d,
+                       const float* gamma, const float* beta, float eps, int32_t relu,
+                       int32_t g, int32_t bits, uint64_t seed, int32_t max_iter,
+                       float* ch_min, float* ch_max, int32_t* assign, int32_t* perm,
+                       int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- offline folding: Sec. 4.2 --------------------------------------------------
+ * Folds the reorder index into LayerNorm's parameters and into the weights of the linear
+ * layer that reads the site: gamma/beta are gathered into the padded cluster-order
+ * layout, W's columns are permuted by perm_in (and its rows by perm_out, the reorder
+ * index of the layer's *output*, when given), every output row is quantized to 4 bits
+ * with its own Eq. 2 parameters over the whole row, and the codes are packed.  Also
+ * emits what the integer form of App. A.4 needs per output channel: the per-cluster code
+ * sums wsum[o,i] = sum_{c in cluster i} wq[o,c] and colterm[o] = sum_i sX_i zX_i wsum[o,i].
+ *
+ *  gamma,beta device fp32 [d] (NULL,NULL: skip the LayerNorm part)
+ *  perm_in    device int32 [K] (K == d), must be a permutation (checked on a host copy
+ *             supplied in perm_in_host, host int32 [K])
+ *  cluster_off,sX,zX  host [g+1],[g],[g]: the site's calibration result
+ *  W          device [N,K] row-major, w_dtype RPTQ_DTYPE_BF16 or RPTQ_DTYPE_F32
+ *  perm_out   device int32 [N] or NULL; output row o' is original row perm_out[o']
+ *  perm_pad   device int32 [K_p] out: source channel of each padded position, -1 = pad
+ *  gamma_pad,beta_pad device fp32 [K_p] out (untouched when gamma == NULL)
+ *  Wq_packed  device out, rptq_weight_bytes(N, K_p)
+ *  sW device fp32 [N], zW device int32 [N], wsum device int32 [N,g], colterm device fp32 [N]
+ */
+int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
+                          const int32_t* perm_in, const int32_t* perm_in_host,
+                          const int32_t* cluster_off, int32_t g, const float* sX, const int32_t* zX,
+                          const void* W, int32_t w_dtype, int32_t N, int32_t K, const int32_t* perm_out,
+                          int32_t* perm_pad, float* gamma_pad, float* beta_pad,
+                          void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm,
+                          void* stream);
+
+/* ---- online stage 1+2: LayerNorm in cluster order + per-cluster quantization -----
+ * For every row t and padded position j with source channel c = perm_pad[j] in cluster i:
+ *     y = ((x[t,c] - mu_t) * rstd_t) * gamma_pad[j] + beta_pad[j]      (Sec. 4.2)
+ *     q = clamp(round(y * inv_s_i) + z_i, -2^(bits-1), 2^(bits-1)-1)  (Eq. 1; App. A.4)
+ * mu_t, rstd_t over the whole row (biased variance) in fp64, rounded once to fp32; the
+ * five elementwise operations are separately rounded fp32; round is half-to-even.
+ * gamma_pad == NULL: no LayerNorm, y = x[t,c] (or max(x,0) when relu != 0), the
+ * quantize-only form used after a linear layer whose rows were permuted offline.
+ *
+ *  x          device bf16 [M,d] row-major, original channel order
+ *  perm_pad   device int32 [K_p] from rptq_fold_reorder
+ *  cluster_off,s,inv_s,z  host [g+1],[g],[g],[g]
+ *  codes_packed device out, rptq_codes_bytes(M, K_p, bits)
+ *  xsum       device int32 [M,g] out or NULL: per-cluster code sums
+ *  rowterm    device fp32 [M] out or NULL: sum_i s_i (xsum[t,i] - n_i z_i), the row sum of
+ *             the de-quantized activation, which the product's zero-point term needs
+ */
+int32_t rptq_ln_quant(const void* x, int64_t M, int32_t d,
+                      const float* gamma_pad, const float* beta_pad, float eps, int32_t relu,
+                      const int32_t* perm_pad, const int32_t* cluster_off, int32_t g,
+                      const float* s, const float* inv_s, const int32_t* z, int32_t bits,
+                      void* codes_packed, int32_t* xsum, float* rowterm, void* stream);
+
+/* ---- online stage 3: cluster-wise integer product (App. A.4, second method) ------
+ * Per cluster i the int32 product P_i[t,o] = sum_{c in i} xq[t,c] wq[o,c] runs on int8
+ * MFMA; with the zero-point terms of App. A.4 the result is
+ *   Y[t,o] = sW_o * ( sum_i sX_i P_i[t,o] - colterm[o] - zW_o * rowterm[t] )
+ * which equals sum_i sX_i sW_o Yq_i with
+ *   Yq_i = P_i - zX_i wsum[o,i] - zW_o xsum[t,i] + n_i zX_i zW_o.
+ * Rows up to 32 take the weight-streaming kernel, larger M the LDS-tiled one.
+ *
+ *  codes_packed device, M rows, `bits` in {3,4,8};  Wq_packed device (N, K_p)
+ *  cluster_off,sX host [g+1],[g];  sW,colterm device fp32 [N]; zW device int32 [N]
+ *  rowterm    device fp32 [M]
+ *  y          device out [M,N] row-major, y_dtype RPTQ_DTYPE_BF16 or RPTQ_DTYPE_F32
+ */
+int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
+                          const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                          const float* sX, const float* sW, const int32_t* zW,
+                          const float* colterm, const float* rowterm,
+                          void* y, int32_t y_dtype, void* stream);
+
+/* ---- helpers for verification (not on the timed path) ---------------------------- */
+
+/* The literal per-cluster integers Yq_i of App. A.4 from the same MFMA main loop:
+ * yq device int32 [g,M,N].  zX host [g]; zW, xsum, wsum device. */
+int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t bits,
+                                   const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                   const int32_t* zX, const int32_t* zW, const int32_t* xsum,
+                                   const int32_t* wsum, int32_t* yq, void* stream);
+/* Packed activation codes -> int8 [rows,K] in cluster order with padding removed. */
+int32_t rptq_unpack_codes(const void* codes_packed, int64_t rows, const int32_t* cluster_off, int32_t g,
+                          int32_t bits, int8_t* out, void* stream);
+/* Packed weights -> int8 [N,K] in cluster order with padding removed. */
+int32_t rptq_unpack_weights(const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                            int8_t* out, void* stream);
+/* Per-channel min/max part of rptq_calibrate alone (device results, fp32 [d] each);
+ * asynchronous.  workspace as for rptq_calibrate. */
+int32_t rptq_channel_minmax(const void* const* x_batches, const int64_t* rows, int32_t n_batches, int32_t d,
+                            const float* gamma, const float* beta, float eps, int32_t relu,
+                            float* ch_min_dev, float* ch_max_dev, void* workspace, size_t workspace_bytes,
+                            void* stream);
+/* Host-only part of rptq_calibrate: K-Means, reorder index, parameters from given min/max. */
+int32_t rptq_cluster_channels(const float* ch_min, const float* ch_max, int32_t d, int32_t g, int32_t bits,
+                              uint64_t seed, int32_t max_iter, int32_t* assign, int32_t* perm,
+                              int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff);
+
+const char* rptq_strerror(int32_t status);
+int32_t rptq_last_hip_error(void);
+const char* rptq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RPTQ_H */

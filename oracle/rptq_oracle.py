@@ -120,7 +120,8 @@ def layernorm_f32(x, gamma, beta, eps: float):
 
     Returns (y fp32 [M,d], fragile bool [M]).  A row is fragile when its
     float64 mean or rstd lies so close to an fp32 rounding boundary that a
-    different summation order could round it the other way.
+    different summation order (mean) or an algebraically equal variance
+    formula (rstd) could round it the other way.
     """
     x = np.asarray(x, dtype=F32)
     d = x.shape[-1]
@@ -130,8 +131,14 @@ def layernorm_f32(x, gamma, beta, eps: float):
     var = (dev * dev).sum(axis=-1) / d
     rstd = 1.0 / np.sqrt(var + float(eps))
     mean_abs = np.abs(xd).sum(axis=-1) / d
-    fragile = (_fp32_midpoint_distance(mu) < FRAGILE_REL * np.maximum(mean_abs, 1e-300)) | (
-        _fp32_midpoint_distance(rstd) < FRAGILE_REL * rstd)
+    # bf16 inputs are multiples of their smallest element's ulp q; while sum|x| < 2^52 q every
+    # partial sum in any order is exact in float64, so the mean cannot depend on the order.
+    mag = np.where(xd != 0.0, np.abs(xd), np.inf)
+    q = np.exp2(np.floor(np.log2(mag.min(axis=-1))) - 7.0)
+    order_free = ~np.isfinite(q) | (mean_abs * d < 2.0 ** 52 * q)
+    ratio = 1.0 + mu * mu / np.maximum(var, 1e-300)
+    fragile = (~order_free & (_fp32_midpoint_distance(mu) < FRAGILE_REL * np.maximum(mean_abs, 1e-300))) | (
+        _fp32_midpoint_distance(rstd) < FRAGILE_REL * rstd * np.minimum(ratio, 1e30))
     mu32 = mu.astype(F32)[..., None]
     rstd32 = rstd.astype(F32)[..., None]
     t = x - mu32

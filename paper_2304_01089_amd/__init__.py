@@ -1,0 +1,31 @@
+"""MI355X (gfx950) implementation of the RPTQ inference hot path.
+
+The product is the C-ABI library `librptq.so` (see include/rptq.h); this package is its
+thin Python binding: same entry-point names, argument marshalling only.  PyTorch supplies
+device memory and streams.  There is no CPU fallback: calling any entry point without the
+built library raises.
+"""
+from .binding import (  # noqa: F401
+    RptqError,
+    library_path,
+    load_library,
+    rptq_padded_k,
+    rptq_codes_bytes,
+    rptq_weight_bytes,
+    rptq_calibrate_workspace_bytes,
+    rptq_cluster_channels,
+    rptq_channel_minmax,
+    rptq_calibrate,
+    rptq_fold_reorder,
+    rptq_ln_quant,
+    rptq_cluster_gemm,
+    rptq_cluster_gemm_partials,
+    rptq_unpack_codes,
+    rptq_unpack_weights,
+    rptq_strerror,
+    rptq_version,
+    EXPORTED_SYMBOLS,
+    DTYPE_BF16,
+    DTYPE_F32,
+)
+from .layer import Calibration, FoldedLinear, calibrate_site, fold_linear, ln_quant, cluster_gemm  # noqa: F401

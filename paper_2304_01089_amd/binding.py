@@ -1,0 +1,303 @@
+"""ctypes binding of librptq.so: one Python function per C entry point, same names.
+
+Arguments are torch tensors (device memory) or numpy arrays / python sequences (host
+tables); every function only checks dtypes, extracts pointers and calls the library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+DTYPE_BF16 = 0
+DTYPE_F32 = 1
+
+EXPORTED_SYMBOLS = (
+    "rptq_padded_k", "rptq_codes_bytes", "rptq_weight_bytes", "rptq_calibrate_workspace_bytes",
+    "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_cluster_gemm",
+    "rptq_cluster_gemm_partials", "rptq_unpack_codes", "rptq_unpack_weights", "rptq_channel_minmax",
+    "rptq_cluster_channels", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
+)
+
+_LIB = None
+
+
+class RptqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = "%s failed: status %d" % (where, status)
+        try:
+            msg += " (%s)" % rptq_strerror(status)
+            if status == -8:
+                msg += " hip error %d" % load_library().rptq_last_hip_error()
+        except Exception:
+            pass
+        super().__init__(msg)
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "librptq.so")
+
+
+def load_library():
+    """Loads the built library; raises if it has not been built (no fallback exists)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError("librptq.so is not built (%s): run `python -m paper_2304_01089_amd.build`" % path)
+    lib = C.CDLL(path)
+    vp, i32, i64, u64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_size_t
+    sig = {
+        "rptq_padded_k": (i32, [vp, i32, vp]),
+        "rptq_codes_bytes": (sz, [i64, i32, i32]),
+        "rptq_weight_bytes": (sz, [i32, i32]),
+        "rptq_calibrate_workspace_bytes": (sz, [i32]),
+        "rptq_calibrate": (i32, [vp, vp, i32, i32, vp, vp, f32, i32, i32, i32, u64, i32,
+                                 vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "rptq_fold_reorder": (i32, [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32, i32, vp,
+                                    vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_ln_quant": (i32, [vp, i64, i32, vp, vp, f32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "rptq_cluster_gemm": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, vp]),
+        "rptq_cluster_gemm_partials": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp]),
+        "rptq_unpack_codes": (i32, [vp, i64, vp, i32, i32, vp, vp]),
+        "rptq_unpack_weights": (i32, [vp, i32, vp, i32, vp, vp]),
+        "rptq_channel_minmax": (i32, [vp, vp, i32, i32, vp, vp, f32, i32, vp, vp, vp, sz, vp]),
+        "rptq_cluster_channels": (i32, [vp, vp, i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_strerror": (C.c_char_p, [i32]),
+        "rptq_last_hip_error": (i32, []),
+        "rptq_version": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _LIB = lib
+    return lib
+
+
+# --------------------------------------------------------------------------------------
+# marshalling helpers
+# --------------------------------------------------------------------------------------
+def _dev(t, dtype=None, allow_none=False):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        if allow_none:
+            return None
+        raise ValueError("missing device tensor")
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def _host(a, dtype):
+    arr = np.ascontiguousarray(a, dtype=dtype)
+    return arr, arr.ctypes.data_as(C.c_void_p)
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise RptqError(status, where)
+
+
+# --------------------------------------------------------------------------------------
+# entry points
+# --------------------------------------------------------------------------------------
+def rptq_strerror(status: int) -> str:
+    return load_library().rptq_strerror(int(status)).decode()
+
+
+def rptq_version() -> str:
+    return load_library().rptq_version().decode()
+
+
+def rptq_padded_k(cluster_off) -> int:
+    off, p = _host(cluster_off, np.int32)
+    out = C.c_int32(0)
+    _check(load_library().rptq_padded_k(p, len(off) - 1, C.byref(out)), "rptq_padded_k")
+    return out.value
+
+
+def rptq_codes_bytes(M: int, k_padded: int, bits: int) -> int:
+    return load_library().rptq_codes_bytes(M, k_padded, bits)
+
+
+def rptq_weight_bytes(N: int, k_padded: int) -> int:
+    return load_library().rptq_weight_bytes(N, k_padded)
+
+
+def rptq_calibrate_workspace_bytes(d: int) -> int:
+    return load_library().rptq_calibrate_workspace_bytes(d)
+
+
+def rptq_cluster_channels(ch_min, ch_max, g: int, bits: int, seed: int = 0, max_iter: int = 100):
+    """Host-only K-Means + reorder index + parameters.  Returns a dict of numpy arrays."""
+    cmin, pmin = _host(ch_min, np.float32)
+    cmax, pmax = _host(ch_max, np.float32)
+    d = cmin.shape[0]
+    assign = np.empty(d, np.int32)
+    perm = np.empty(d, np.int32)
+    off = np.zeros(g + 1, np.int32)
+    s = np.zeros(g, np.float32)
+    inv_s = np.zeros(g, np.float32)
+    z = np.zeros(g, np.int32)
+    g_eff = C.c_int32(0)
+    st = load_library().rptq_cluster_channels(
+        pmin, pmax, d, g, bits, seed, max_iter, assign.ctypes.data_as(C.c_void_p), perm.ctypes.data_as(C.c_void_p),
+        off.ctypes.data_as(C.c_void_p), s.ctypes.data_as(C.c_void_p), inv_s.ctypes.data_as(C.c_void_p),
+        z.ctypes.data_as(C.c_void_p), C.byref(g_eff))
+    _check(st, "rptq_cluster_channels")
+    ge = g_eff.value
+    return dict(ch_min=cmin, ch_max=cmax, assign=assign, perm=perm, cluster_off=off[:ge + 1].copy(),
+                s=s[:ge].copy(), inv_s=inv_s[:ge].copy(), z=z[:ge].copy(), g_eff=ge)
+
+
+def _batches(x_batches):
+    import torch
+    ptrs = (C.c_void_p * len(x_batches))()
+    rows = (C.c_int64 * len(x_batches))()
+    d = None
+    for i, xb in enumerate(x_batches):
+        if xb.dtype != torch.bfloat16 or xb.dim() != 2:
+            raise ValueError("calibration batches must be bf16 [rows, d]")
+        ptrs[i] = _dev(xb).value
+        rows[i] = xb.shape[0]
+        d = xb.shape[1] if d is None else d
+        if xb.shape[1] != d:
+            raise ValueError("calibration batches disagree on d")
+    return ptrs, rows, d
+
+
+def rptq_channel_minmax(x_batches, gamma, beta, eps: float, relu: bool, ch_min_dev, ch_max_dev, workspace,
+                        stream=None):
+    import torch
+    ptrs, rows, d = _batches(x_batches)
+    st = load_library().rptq_channel_minmax(
+        ptrs, rows, len(x_batches), d, _dev(gamma, torch.float32, True), _dev(beta, torch.float32, True),
+        float(eps), int(bool(relu)), _dev(ch_min_dev, torch.float32), _dev(ch_max_dev, torch.float32),
+        _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "rptq_channel_minmax")
+
+
+def rptq_calibrate(x_batches, gamma, beta, eps: float, relu: bool, g: int, bits: int, seed: int = 0,
+                   max_iter: int = 100, workspace=None, stream=None):
+    """Sec. 4.1 calibration.  Returns a dict of host numpy arrays (see rptq.h)."""
+    import torch
+    ptrs, rows, d = _batches(x_batches)
+    if workspace is None:
+        workspace = torch.empty(rptq_calibrate_workspace_bytes(d), dtype=torch.uint8, device=x_batches[0].device)
+    ch_min = np.empty(d, np.float32)
+    ch_max = np.empty(d, np.float32)
+    assign = np.empty(d, np.int32)
+    perm = np.empty(d, np.int32)
+    off = np.zeros(g + 1, np.int32)
+    s = np.zeros(g, np.float32)
+    inv_s = np.zeros(g, np.float32)
+    z = np.zeros(g, np.int32)
+    g_eff = C.c_int32(0)
+    vp = C.c_void_p
+    st = load_library().rptq_calibrate(
+        ptrs, rows, len(x_batches), d, _dev(gamma, torch.float32, True), _dev(beta, torch.float32, True),
+        float(eps), int(bool(relu)), g, bits, seed, max_iter,
+        ch_min.ctypes.data_as(vp), ch_max.ctypes.data_as(vp), assign.ctypes.data_as(vp), perm.ctypes.data_as(vp),
+        off.ctypes.data_as(vp), s.ctypes.data_as(vp), inv_s.ctypes.data_as(vp), z.ctypes.data_as(vp),
+        C.byref(g_eff), _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "rptq_calibrate")
+    ge = g_eff.value
+    return dict(ch_min=ch_min, ch_max=ch_max, assign=assign, perm=perm, cluster_off=off[:ge + 1].copy(),
+                s=s[:ge].copy(), inv_s=inv_s[:ge].copy(), z=z[:ge].copy(), g_eff=ge)
+
+
+def rptq_fold_reorder(gamma, beta, d: int, perm_in_dev, perm_in_host, cluster_off, sX, zX, W, N: int, K: int,
+                      perm_out, perm_pad, gamma_pad, beta_pad, Wq_packed, sW, zW, wsum, colterm, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    g = len(off) - 1
+    ph, pph = _host(perm_in_host, np.int32)
+    sx, psx = _host(sX if sX is not None else np.ones(g), np.float32)
+    zx, pzx = _host(zX if zX is not None else np.zeros(g), np.int32)
+    w_dtype = DTYPE_BF16
+    if W is not None:
+        if W.dtype == torch.float32:
+            w_dtype = DTYPE_F32
+        elif W.dtype != torch.bfloat16:
+            raise ValueError("W must be bf16 or fp32")
+    st = load_library().rptq_fold_reorder(
+        _dev(gamma, torch.float32, True), _dev(beta, torch.float32, True), d,
+        _dev(perm_in_dev, torch.int32), pph, poff, g, psx, pzx,
+        _dev(W, None, True), w_dtype, N, K, _dev(perm_out, torch.int32, True),
+        _dev(perm_pad, torch.int32), _dev(gamma_pad, torch.float32, True), _dev(beta_pad, torch.float32, True),
+        _dev(Wq_packed, None, True), _dev(sW, torch.float32, True), _dev(zW, torch.int32, True),
+        _dev(wsum, torch.int32, True), _dev(colterm, torch.float32, True), _stream(stream))
+    _check(st, "rptq_fold_reorder")
+
+
+def rptq_ln_quant(x, M: int, d: int, gamma_pad, beta_pad, eps: float, relu: bool, perm_pad, cluster_off,
+                  s, inv_s, z, bits: int, codes_packed, xsum=None, rowterm=None, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    sa, ps = _host(s, np.float32)
+    ia, pi = _host(inv_s, np.float32)
+    za, pz = _host(z, np.int32)
+    st = load_library().rptq_ln_quant(
+        _dev(x, torch.bfloat16), M, d, _dev(gamma_pad, torch.float32, True), _dev(beta_pad, torch.float32, True),
+        float(eps), int(bool(relu)), _dev(perm_pad, torch.int32), poff, len(off) - 1, ps, pi, pz, bits,
+        _dev(codes_packed), _dev(xsum, torch.int32, True), _dev(rowterm, torch.float32, True), _stream(stream))
+    _check(st, "rptq_ln_quant")
+
+
+def rptq_cluster_gemm(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, sX, sW, zW, colterm,
+                      rowterm, y, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    sx, psx = _host(sX, np.float32)
+    if y.dtype == torch.float32:
+        y_dtype = DTYPE_F32
+    elif y.dtype == torch.bfloat16:
+        y_dtype = DTYPE_BF16
+    else:
+        raise ValueError("y must be bf16 or fp32")
+    st = load_library().rptq_cluster_gemm(
+        _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, psx,
+        _dev(sW, torch.float32), _dev(zW, torch.int32), _dev(colterm, torch.float32),
+        _dev(rowterm, torch.float32), _dev(y), y_dtype, _stream(stream))
+    _check(st, "rptq_cluster_gemm")
+
+
+def rptq_cluster_gemm_partials(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, zX, zW, xsum,
+                               wsum, yq, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    zx, pzx = _host(zX, np.int32)
+    st = load_library().rptq_cluster_gemm_partials(
+        _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, pzx, _dev(zW, torch.int32),
+        _dev(xsum, torch.int32), _dev(wsum, torch.int32), _dev(yq, torch.int32), _stream(stream))
+    _check(st, "rptq_cluster_gemm_partials")
+
+
+def rptq_unpack_codes(codes_packed, rows: int, cluster_off, bits: int, out, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    st = load_library().rptq_unpack_codes(_dev(codes_packed), rows, poff, len(off) - 1, bits,
+                                          _dev(out, torch.int8), _stream(stream))
+    _check(st, "rptq_unpack_codes")
+
+
+def rptq_unpack_weights(Wq_packed, N: int, cluster_off, out, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    st = load_library().rptq_unpack_weights(_dev(Wq_packed), N, poff, len(off) - 1, _dev(out, torch.int8),
+                                            _stream(stream))
+    _check(st, "rptq_unpack_weights")

@@ -1,0 +1,201 @@
+// extern "C" entry points of librptq: host-side validation, then the kernel launchers.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "rptq_internal.h"
+
+using namespace rptq;
+
+namespace {
+
+int32_t make_quant_tab(const ClusterGeom& geom, const float* s, const float* inv_s, const int32_t* z, int bits,
+                       QuantTab* qt) {
+  const int qmin = -(1 << (bits - 1)), qmax = (1 << (bits - 1)) - 1;
+  for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i) {
+    const bool in = i < geom.g;
+    if (in) {
+      if (!(std::isfinite(inv_s[i]) && inv_s[i] > 0.0f)) return RPTQ_ERR_RANGE;
+      if (z[i] > kZLimit || z[i] < -kZLimit) return RPTQ_ERR_RANGE;
+      if (s && !(std::isfinite(s[i]) && s[i] > 0.0f)) return RPTQ_ERR_RANGE;
+    }
+    qt->inv_s[i] = in ? inv_s[i] : 1.0f;
+    qt->z[i] = in ? z[i] : 0;
+    qt->lo[i] = static_cast<float>(qmin - qt->z[i]);
+    qt->hi[i] = static_cast<float>(qmax - qt->z[i]);
+    qt->zb[i] = qt->z[i] - qmin;
+    qt->s[i] = (in && s) ? s[i] : 0.0f;
+  }
+  return RPTQ_OK;
+}
+
+int32_t check_permutation(const int32_t* perm, int32_t n) {
+  std::vector<uint8_t> seen(static_cast<size_t>(n), 0);
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t p = perm[i];
+    if (p < 0 || p >= n || seen[p]) return RPTQ_ERR_PERM;
+    seen[p] = 1;
+  }
+  return RPTQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t rptq_channel_minmax(const void* const* x_batches, const int64_t* rows, int32_t n_batches, int32_t d,
+                            const float* gamma, const float* beta, float eps, int32_t relu,
+                            float* ch_min_dev, float* ch_max_dev, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (!x_batches || !rows || !ch_min_dev || !ch_max_dev || !workspace) return RPTQ_ERR_NULL;
+  if ((gamma == nullptr) != (beta == nullptr)) return RPTQ_ERR_NULL;
+  if (n_batches < 1 || d < 8 || d > RPTQ_MAX_CHANNELS || d % 8 != 0) return RPTQ_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return RPTQ_ERR_RANGE;
+  int64_t total = 0;
+  for (int b = 0; b < n_batches; ++b) {
+    if (rows[b] < 0) return RPTQ_ERR_SHAPE;
+    if (rows[b] > 0 && !x_batches[b]) return RPTQ_ERR_NULL;
+    if (!aligned16(x_batches[b])) return RPTQ_ERR_ALIGN;
+    total += rows[b];
+  }
+  if (total < 1) return RPTQ_ERR_SHAPE;
+  if (workspace_bytes < static_cast<size_t>(d) * 2 * sizeof(uint32_t)) return RPTQ_ERR_WORKSPACE;
+  if (!aligned16(workspace) || !aligned16(gamma) || !aligned16(beta)) return RPTQ_ERR_ALIGN;
+  return launch_channel_minmax(x_batches, rows, n_batches, d, gamma, beta, eps, relu, ch_min_dev, ch_max_dev,
+                               static_cast<uint32_t*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_calibrate(const void* const* x_batches, const int64_t* rows, int32_t n_batches, int32_t d,
+                       const float* gamma, const float* beta, float eps, int32_t relu,
+                       int32_t g, int32_t bits, uint64_t seed, int32_t max_iter,
+                       float* ch_min, float* ch_max, int32_t* assign, int32_t* perm,
+                       int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!ch_min || !ch_max || !assign || !perm || !cluster_off || !s || !inv_s || !z || !g_eff) return RPTQ_ERR_NULL;
+  if (d < 1 || g < 1 || g > d || g > RPTQ_MAX_CLUSTERS || max_iter < 1) return RPTQ_ERR_SHAPE;
+  if (int32_t st = check_bits(bits)) return st;
+  if (workspace_bytes < rptq_calibrate_workspace_bytes(d) || rptq_calibrate_workspace_bytes(d) == 0)
+    return workspace ? RPTQ_ERR_WORKSPACE : RPTQ_ERR_NULL;
+  float* dev_min = reinterpret_cast<float*>(static_cast<uint32_t*>(workspace) + 2 * static_cast<size_t>(d));
+  float* dev_max = dev_min + d;
+  if (int32_t st = rptq_channel_minmax(x_batches, rows, n_batches, d, gamma, beta, eps, relu, dev_min, dev_max,
+                                       workspace, workspace_bytes, stream))
+    return st;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  RPTQ_HIP(hipMemcpyAsync(ch_min, dev_min, sizeof(float) * d, hipMemcpyDeviceToHost, hs));
+  RPTQ_HIP(hipMemcpyAsync(ch_max, dev_max, sizeof(float) * d, hipMemcpyDeviceToHost, hs));
+  RPTQ_HIP(hipStreamSynchronize(hs));
+  return cluster_channels(ch_min, ch_max, d, g, bits, seed, max_iter, assign, perm, cluster_off, s, inv_s, z, g_eff);
+}
+
+int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
+                          const int32_t* perm_in, const int32_t* perm_in_host,
+                          const int32_t* cluster_off, int32_t g, const float* sX, const int32_t* zX,
+                          const void* W, int32_t w_dtype, int32_t N, int32_t K, const int32_t* perm_out,
+                          int32_t* perm_pad, float* gamma_pad, float* beta_pad,
+                          void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm,
+                          void* stream) {
+  if (!perm_in || !perm_in_host || !perm_pad) return RPTQ_ERR_NULL;
+  if ((gamma == nullptr) != (beta == nullptr)) return RPTQ_ERR_NULL;
+  if (gamma && (!gamma_pad || !beta_pad)) return RPTQ_ERR_NULL;
+  if (W && (!Wq_packed || !sW || !zW || !wsum || !colterm || !sX || !zX)) return RPTQ_ERR_NULL;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (d < 1 || geom.k != d) return RPTQ_ERR_SHAPE;
+  if (W) {
+    if (K != d || N < 1) return RPTQ_ERR_SHAPE;
+    if (w_dtype != RPTQ_DTYPE_BF16 && w_dtype != RPTQ_DTYPE_F32) return RPTQ_ERR_SHAPE;
+    for (int i = 0; i < g; ++i) {
+      if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
+      if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
+    }
+  }
+  if (int32_t st = check_permutation(perm_in_host, d)) return st;
+  if (!aligned16(perm_in) || !aligned16(perm_pad) || !aligned16(gamma) || !aligned16(beta) || !aligned16(gamma_pad) ||
+      !aligned16(beta_pad) || !aligned16(W) || !aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) ||
+      !aligned16(wsum) || !aligned16(colterm) || !aligned16(perm_out))
+    return RPTQ_ERR_ALIGN;
+  return launch_fold(gamma, beta, perm_in, geom, sX, zX, W, w_dtype, N, perm_out, perm_pad, gamma_pad, beta_pad,
+                     Wq_packed, sW, zW, wsum, colterm, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_ln_quant(const void* x, int64_t M, int32_t d,
+                      const float* gamma_pad, const float* beta_pad, float eps, int32_t relu,
+                      const int32_t* perm_pad, const int32_t* cluster_off, int32_t g,
+                      const float* s, const float* inv_s, const int32_t* z, int32_t bits,
+                      void* codes_packed, int32_t* xsum, float* rowterm, void* stream) {
+  if (!x || !perm_pad || !inv_s || !z || !codes_packed) return RPTQ_ERR_NULL;
+  if ((gamma_pad == nullptr) != (beta_pad == nullptr)) return RPTQ_ERR_NULL;
+  if (rowterm && !s) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || d < 8 || d % 8 != 0 || geom.k != d) return RPTQ_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return RPTQ_ERR_RANGE;
+  QuantTab qt;
+  if (int32_t st = make_quant_tab(geom, s, inv_s, z, bits, &qt)) return st;
+  if (!aligned16(x) || !aligned16(gamma_pad) || !aligned16(beta_pad) || !aligned16(perm_pad) ||
+      !aligned16(codes_packed) || !aligned16(xsum) || !aligned16(rowterm))
+    return RPTQ_ERR_ALIGN;
+  return launch_ln_quant(x, M, d, gamma_pad, beta_pad, eps, relu, perm_pad, geom, qt, bits, codes_packed, xsum,
+                         rowterm, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
+                          const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                          const float* sX, const float* sW, const int32_t* zW,
+                          const float* colterm, const float* rowterm,
+                          void* y, int32_t y_dtype, void* stream) {
+  if (!codes_packed || !Wq_packed || !sX || !sW || !zW || !colterm || !rowterm || !y) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || N < 1) return RPTQ_ERR_SHAPE;
+  if (y_dtype != RPTQ_DTYPE_BF16 && y_dtype != RPTQ_DTYPE_F32) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i)
+    if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
+  if (!aligned16(codes_packed) || !aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) || !aligned16(colterm) ||
+      !aligned16(rowterm) || !aligned16(y))
+    return RPTQ_ERR_ALIGN;
+  return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, sX, sW, zW, colterm, rowterm, y, y_dtype, nullptr,
+                     nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t bits,
+                                   const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                   const int32_t* zX, const int32_t* zW, const int32_t* xsum,
+                                   const int32_t* wsum, int32_t* yq, void* stream) {
+  if (!codes_packed || !Wq_packed || !zX || !zW || !xsum || !wsum || !yq) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || N < 1) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i)
+    if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
+  if (!aligned16(codes_packed) || !aligned16(Wq_packed) || !aligned16(zW) || !aligned16(xsum) || !aligned16(wsum) ||
+      !aligned16(yq))
+    return RPTQ_ERR_ALIGN;
+  return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, nullptr, nullptr, zW, nullptr, nullptr, nullptr,
+                     RPTQ_DTYPE_F32, zX, xsum, wsum, yq, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_unpack_codes(const void* codes_packed, int64_t rows, const int32_t* cluster_off, int32_t g,
+                          int32_t bits, int8_t* out, void* stream) {
+  if (!codes_packed || !out) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (rows < 0) return RPTQ_ERR_SHAPE;
+  return launch_unpack_codes(codes_packed, rows, geom, bits, out, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_unpack_weights(const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                            int8_t* out, void* stream) {
+  if (!Wq_packed || !out) return RPTQ_ERR_NULL;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (N < 1) return RPTQ_ERR_SHAPE;
+  return launch_unpack_weights(Wq_packed, N, geom, out, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,196 @@
+// Offline folding of the reorder index (Sec. 4.2): LayerNorm parameters gathered into the
+// padded cluster-order layout, weight columns permuted by the input reorder index (rows by
+// the output reorder index when given), 4-bit Min-Max quantization per output channel
+// (Eq. 1, Eq. 2 over the whole row), packing into the MFMA-fragment-major weight layout,
+// and the per-cluster code sums the integer form of App. A.4 needs.
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+#include "rptq_internal.h"
+
+namespace rptq {
+
+__global__ void fold_ln_kernel(const float* gamma, const float* beta, const int32_t* perm_in, ClusterGeom geom,
+                               int32_t* perm_pad, float* gamma_pad, float* beta_pad) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= geom.k_padded) return;
+  int c = -1;
+  if (j < geom.pad_off[geom.g]) {
+    int ci = 0;
+    for (int i = 1; i < geom.g; ++i) ci += (j >= geom.pad_off[i]) ? 1 : 0;
+    const int local = j - geom.pad_off[ci];
+    if (local < geom.off[ci + 1] - geom.off[ci]) c = perm_in[geom.off[ci] + local];
+  }
+  perm_pad[j] = c;
+  if (gamma) {
+    gamma_pad[j] = c >= 0 ? gamma[c] : 0.0f;
+    beta_pad[j] = c >= 0 ? beta[c] : 0.0f;
+  }
+}
+
+// Byte offset of the dword holding padded columns 8u..8u+7 of output row o.
+__device__ __host__ __forceinline__ size_t weight_dword_offset(int o, int u, int k_padded) {
+  const int rb = o >> 5, r = o & 31;
+  const int s = u >> 2, k8 = u & 3, h = k8 >> 1, v = k8 & 1;
+  return ((static_cast<size_t>(rb) * (k_padded / kGroup) + s) * 64 + h * 32 + r) * 8 + v * 4;
+}
+
+struct FoldArgs {
+  const void* W;
+  int32_t w_bf16;
+  int32_t N;
+  int32_t n_padded;
+  const int32_t* perm_out;
+  const int32_t* perm_pad;
+  uint8_t* Wq;
+  float* sW;
+  int32_t* zW;
+  int32_t* wsum;
+  float* colterm;
+};
+
+struct ScaleTab {
+  double sz[RPTQ_MAX_CLUSTERS];     // sX_i * zX_i
+};
+
+__global__ void __launch_bounds__(256) fold_weight_kernel(FoldArgs a, ClusterGeom geom, ScaleTab tab) {
+  __shared__ float red_min[4], red_max[4];
+  __shared__ float sh_inv;
+  __shared__ int32_t sh_z;
+  __shared__ int32_t sh_wsum[RPTQ_MAX_CLUSTERS];
+  const int o = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int n_units = geom.k_padded / 8;
+
+  if (o >= a.N) {                                  // rows added by rounding N up: all-zero codes
+    for (int u = tid; u < n_units; u += blockDim.x)
+      *reinterpret_cast<uint32_t*>(a.Wq + weight_dword_offset(o, u, geom.k_padded)) = 0u;
+    return;
+  }
+  const int64_t src_row = a.perm_out ? a.perm_out[o] : o;
+  const uint16_t* wb = static_cast<const uint16_t*>(a.W) + src_row * geom.k;
+  const float* wf = static_cast<const float*>(a.W) + src_row * geom.k;
+  auto wval = [&](int c) -> float { return a.w_bf16 ? __uint_as_float(static_cast<uint32_t>(wb[c]) << 16) : wf[c]; };
+
+  // ---- Eq. 2 over the whole row ---------------------------------------------------------
+  float lo = __builtin_huge_valf(), hi = -__builtin_huge_valf();
+  for (int c = tid; c < geom.k; c += blockDim.x) {
+    const float w = wval(c);
+    lo = fminf(lo, w);
+    hi = fmaxf(hi, w);
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    lo = fminf(lo, __shfl_xor(lo, m, kWave));
+    hi = fmaxf(hi, __shfl_xor(hi, m, kWave));
+  }
+  if ((tid & 63) == 0) {
+    red_min[tid >> 6] = lo;
+    red_max[tid >> 6] = hi;
+  }
+  if (tid < geom.g) sh_wsum[tid] = 0;
+  __syncthreads();
+  if (tid == 0) {
+    const double l = fminf(fminf(red_min[0], red_min[1]), fminf(red_min[2], red_min[3])) + 0.0f;
+    const double h = fmaxf(fmaxf(red_max[0], red_max[1]), fmaxf(red_max[2], red_max[3])) + 0.0f;
+    double s64, zz;
+    if (h == l) {
+      s64 = 1.0;
+      zz = -rint(l);
+    } else {
+      s64 = (h - l) / 16.0;
+      zz = -rint((h + l) / (2.0 * s64));
+    }
+    const float s32 = static_cast<float>(s64);
+    sh_inv = static_cast<float>(1.0 / static_cast<double>(s32));
+    sh_z = static_cast<int32_t>(zz);
+    a.sW[o] = s32;
+    a.zW[o] = sh_z;
+  }
+  __syncthreads();
+  const float inv = sh_inv;
+  const float zf = static_cast<float>(sh_z);
+
+  // ---- Eq. 1 per weight, pack eight codes per dword ----------------------------------------
+  for (int u = tid; u < n_units; u += blockDim.x) {
+    int q[8];
+    int sum = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = a.perm_pad[u * 8 + e];
+      int code = 0;
+      if (c >= 0) {
+        const float r = __fmul_rn(wval(c), inv);
+        float b = __fadd_rn(rintf(r), zf);
+        b = fminf(fmaxf(b, -8.0f), 7.0f);
+        code = static_cast<int>(b);
+      }
+      q[e] = code;
+      sum += code;
+    }
+    uint32_t word = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) word |= static_cast<uint32_t>(((q[b] & 15) << 4) | (q[4 + b] & 15)) << (8 * b);
+    *reinterpret_cast<uint32_t*>(a.Wq + weight_dword_offset(o, u, geom.k_padded)) = word;
+    int ci = 0;
+    for (int i = 1; i < geom.g; ++i) ci += (u * 8 >= geom.pad_off[i]) ? 1 : 0;
+    atomicAdd(&sh_wsum[ci], sum);
+  }
+  __syncthreads();
+  if (tid < geom.g) a.wsum[static_cast<int64_t>(o) * geom.g + tid] = sh_wsum[tid];
+  if (tid == 0) {
+    double acc = 0.0;
+    for (int i = 0; i < geom.g; ++i) acc += tab.sz[i] * static_cast<double>(sh_wsum[i]);
+    a.colterm[o] = static_cast<float>(acc);
+  }
+}
+
+__global__ void unpack_weights_kernel(const uint8_t* Wq, int N, ClusterGeom geom, int8_t* out) {
+  const int o = blockIdx.x;
+  if (o >= N) return;
+  for (int j = threadIdx.x; j < geom.k; j += blockDim.x) {
+    int ci = 0;
+    for (int i = 1; i < geom.g; ++i) ci += (j >= geom.off[i]) ? 1 : 0;
+    const int pos = geom.pad_off[ci] + (j - geom.off[ci]);
+    const int u = pos >> 3, e = pos & 7;
+    const uint8_t byte = Wq[weight_dword_offset(o, u, geom.k_padded) + (e & 3)];
+    const int nib = (e < 4) ? (byte >> 4) : (byte & 15);
+    out[static_cast<int64_t>(o) * geom.k + j] = static_cast<int8_t>((nib ^ 8) - 8);
+  }
+}
+
+int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_in, const ClusterGeom& geom,
+                    const float* sX, const int32_t* zX, const void* W, int32_t w_dtype, int32_t N,
+                    const int32_t* perm_out, int32_t* perm_pad, float* gamma_pad, float* beta_pad,
+                    void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm, hipStream_t st) {
+  hipLaunchKernelGGL(fold_ln_kernel, dim3((geom.k_padded + 255) / 256), dim3(256), 0, st, gamma, beta, perm_in, geom,
+                     perm_pad, gamma_pad, beta_pad);
+  RPTQ_HIP(hipGetLastError());
+  if (!W) return RPTQ_OK;
+  FoldArgs a;
+  a.W = W;
+  a.w_bf16 = (w_dtype == RPTQ_DTYPE_BF16);
+  a.N = N;
+  a.n_padded = (N + RPTQ_N_ALIGN - 1) / RPTQ_N_ALIGN * RPTQ_N_ALIGN;
+  a.perm_out = perm_out;
+  a.perm_pad = perm_pad;
+  a.Wq = static_cast<uint8_t*>(Wq_packed);
+  a.sW = sW;
+  a.zW = zW;
+  a.wsum = wsum;
+  a.colterm = colterm;
+  ScaleTab tab;
+  for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i)
+    tab.sz[i] = i < geom.g ? static_cast<double>(sX[i]) * static_cast<double>(zX[i]) : 0.0;
+  hipLaunchKernelGGL(fold_weight_kernel, dim3(a.n_padded), dim3(256), 0, st, a, geom, tab);
+  RPTQ_HIP(hipGetLastError());
+  return RPTQ_OK;
+}
+
+int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st) {
+  hipLaunchKernelGGL(unpack_weights_kernel, dim3(N), dim3(256), 0, st, static_cast<const uint8_t*>(Wq), N, geom, out);
+  RPTQ_HIP(hipGetLastError());
+  return RPTQ_OK;
+}
+
+}  // namespace rptq

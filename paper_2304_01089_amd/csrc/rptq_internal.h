@@ -1,0 +1,71 @@
+// Internal declarations shared by the translation units of librptq.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+
+#include "rptq.h"
+
+namespace rptq {
+
+constexpr int kGroup = 32;                 // codes per packed group; cluster padding unit
+constexpr int32_t kZLimit = 1 << 21;       // largest |zero point| the fp32 clamp bounds carry exactly
+
+// Cluster geometry passed to kernels by value (g <= RPTQ_MAX_CLUSTERS).
+struct ClusterGeom {
+  int32_t g;
+  int32_t k;                               // unpadded channel count
+  int32_t k_padded;                        // K_p
+  int32_t off[RPTQ_MAX_CLUSTERS + 1];      // unpadded cluster offsets
+  int32_t pad_off[RPTQ_MAX_CLUSTERS + 1];  // padded start of each cluster; pad_off[g] = end of last cluster
+};
+
+// Per-cluster quantizer constants for the LN+quant kernels.
+struct QuantTab {
+  float inv_s[RPTQ_MAX_CLUSTERS];
+  float lo[RPTQ_MAX_CLUSTERS];             // float(qmin - z): clamp bounds applied before rounding
+  float hi[RPTQ_MAX_CLUSTERS];             // float(qmax - z)
+  int32_t zb[RPTQ_MAX_CLUSTERS];           // z - qmin: turns round(r) into the biased code
+  float s[RPTQ_MAX_CLUSTERS];
+  int32_t z[RPTQ_MAX_CLUSTERS];
+};
+
+// Validation helpers (host.cpp).  All return an rptq_status.
+int32_t check_clusters(const int32_t* cluster_off, int32_t g, ClusterGeom* geom);
+int32_t check_bits(int32_t bits);
+bool aligned16(const void* p);
+
+// Records a failed HIP call for rptq_last_hip_error() and returns RPTQ_ERR_HIP.
+int32_t hip_fail(hipError_t e);
+#define RPTQ_HIP(expr)                                   \
+  do {                                                   \
+    hipError_t e_ = (expr);                              \
+    if (e_ != hipSuccess) return ::rptq::hip_fail(e_);   \
+  } while (0)
+
+// Host clustering (host.cpp), exposed through rptq_cluster_channels.
+int32_t cluster_channels(const float* ch_min, const float* ch_max, int32_t d, int32_t g, int32_t bits,
+                         uint64_t seed, int32_t max_iter, int32_t* assign, int32_t* perm,
+                         int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff);
+
+// Kernel launchers (one per .hip file).  Arguments are already validated.
+int32_t launch_channel_minmax(const void* const* x_batches, const int64_t* rows, int32_t n_batches, int32_t d,
+                              const float* gamma, const float* beta, float eps, int32_t relu,
+                              float* ch_min_dev, float* ch_max_dev, uint32_t* keys, hipStream_t st);
+int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_in, const ClusterGeom& geom,
+                    const float* sX, const int32_t* zX, const void* W, int32_t w_dtype, int32_t N,
+                    const int32_t* perm_out, int32_t* perm_pad, float* gamma_pad, float* beta_pad,
+                    void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm, hipStream_t st);
+int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_pad, const float* beta_pad,
+                        float eps, int32_t relu, const int32_t* perm_pad, const ClusterGeom& geom,
+                        const QuantTab& qt, int32_t bits, void* codes, int32_t* xsum, float* rowterm,
+                        hipStream_t st);
+int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, int32_t N,
+                    const ClusterGeom& geom, const float* sX, const float* sW, const int32_t* zW,
+                    const float* colterm, const float* rowterm, void* y, int32_t y_dtype,
+                    const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq, hipStream_t st);
+int32_t launch_unpack_codes(const void* codes, int64_t rows, const ClusterGeom& geom, int32_t bits, int8_t* out,
+                            hipStream_t st);
+int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st);
+
+}  // namespace rptq

@@ -1,0 +1,97 @@
+"""Buffer management around the C entry points: allocates the device tensors a site and
+its linear layers need (torch is used for memory only) and calls the library."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+
+from . import binding as B
+
+
+@dataclass
+class Calibration:
+    """Host result of rptq_calibrate for one site, plus device copies the kernels read."""
+    d: int
+    bits: int
+    ch_min: np.ndarray
+    ch_max: np.ndarray
+    assign: np.ndarray
+    perm: np.ndarray
+    cluster_off: np.ndarray
+    s: np.ndarray
+    inv_s: np.ndarray
+    z: np.ndarray
+    g_eff: int
+    k_padded: int
+    perm_dev: object = None
+    perm_pad: object = None
+    gamma_pad: object = None
+    beta_pad: object = None
+
+
+@dataclass
+class FoldedLinear:
+    N: int
+    Wq: object
+    sW: object
+    zW: object
+    wsum: object
+    colterm: object
+
+
+def calibrate_site(x_batches, gamma, beta, eps, relu, g, bits, seed=0, max_iter=100) -> Calibration:
+    import torch
+    res = B.rptq_calibrate(x_batches, gamma, beta, eps, relu, g, bits, seed, max_iter)
+    d = x_batches[0].shape[1]
+    cal = Calibration(d=d, bits=bits, k_padded=B.rptq_padded_k(res["cluster_off"]), **res)
+    dev = x_batches[0].device
+    cal.perm_dev = torch.from_numpy(cal.perm).to(dev)
+    cal.perm_pad = torch.empty(cal.k_padded, dtype=torch.int32, device=dev)
+    if gamma is not None:
+        cal.gamma_pad = torch.empty(cal.k_padded, dtype=torch.float32, device=dev)
+        cal.beta_pad = torch.empty(cal.k_padded, dtype=torch.float32, device=dev)
+    B.rptq_fold_reorder(gamma, beta, d, cal.perm_dev, cal.perm, cal.cluster_off, None, None, None, 0, d, None,
+                        cal.perm_pad, cal.gamma_pad, cal.beta_pad, None, None, None, None, None)
+    return cal
+
+
+def fold_linear(cal: Calibration, W, perm_out=None) -> FoldedLinear:
+    import torch
+    N, K = W.shape
+    dev = W.device
+    out = FoldedLinear(
+        N=N,
+        Wq=torch.empty(B.rptq_weight_bytes(N, cal.k_padded), dtype=torch.uint8, device=dev),
+        sW=torch.empty(N, dtype=torch.float32, device=dev),
+        zW=torch.empty(N, dtype=torch.int32, device=dev),
+        wsum=torch.empty((N, cal.g_eff), dtype=torch.int32, device=dev),
+        colterm=torch.empty(N, dtype=torch.float32, device=dev))
+    B.rptq_fold_reorder(None, None, cal.d, cal.perm_dev, cal.perm, cal.cluster_off, cal.s, cal.z, W, N, K, perm_out,
+                        cal.perm_pad, None, None, out.Wq, out.sW, out.zW, out.wsum, out.colterm)
+    return out
+
+
+def ln_quant(cal: Calibration, x, eps=1e-5, relu=False, codes=None, xsum=None, rowterm=None, want_xsum=False):
+    import torch
+    M = x.shape[0]
+    dev = x.device
+    if codes is None:
+        codes = torch.empty(B.rptq_codes_bytes(M, cal.k_padded, cal.bits), dtype=torch.uint8, device=dev)
+    if rowterm is None:
+        rowterm = torch.empty(M, dtype=torch.float32, device=dev)
+    if xsum is None and want_xsum:
+        xsum = torch.empty((M, cal.g_eff), dtype=torch.int32, device=dev)
+    B.rptq_ln_quant(x, M, cal.d, cal.gamma_pad, cal.beta_pad, eps, relu, cal.perm_pad, cal.cluster_off,
+                    cal.s, cal.inv_s, cal.z, cal.bits, codes, xsum, rowterm)
+    return codes, xsum, rowterm
+
+
+def cluster_gemm(cal: Calibration, lin: FoldedLinear, codes, rowterm, M, y=None, dtype=None):
+    import torch
+    if y is None:
+        y = torch.empty((M, lin.N), dtype=dtype or torch.bfloat16, device=codes.device)
+    B.rptq_cluster_gemm(codes, M, cal.bits, lin.Wq, lin.N, cal.cluster_off, cal.s, lin.sW, lin.zW, lin.colterm,
+                        rowterm, y)
+    return y

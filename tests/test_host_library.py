@@ -1,0 +1,126 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, its
+host logic (sizes, validation, clustering) agrees with the oracle, and the packed-layout
+codec used by the GPU tests round-trips.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2304_01089_amd as rp
+import workloads as w
+from oracle import rptq_oracle as o
+
+import packfmt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rp.library_path()):
+        from paper_2304_01089_amd.build import build_library
+        build_library()
+    return rp.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "rptq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rptq_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(rp.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert rp.rptq_version().startswith("rptq-gfx950")
+
+
+def test_size_queries():
+    assert rp.rptq_padded_k([0, 5, 40, 100]) == 256            # 32 + 64 + 64 = 160 -> 256
+    assert rp.rptq_padded_k([0, 128]) == 128
+    assert rp.rptq_padded_k([0, 129]) == 256
+    assert rp.rptq_codes_bytes(10, 256, 4) == 10 * 128
+    assert rp.rptq_codes_bytes(10, 256, 3) == 10 * 96
+    assert rp.rptq_codes_bytes(10, 256, 8) == 10 * 256
+    assert rp.rptq_codes_bytes(10, 256, 5) == 0
+    assert rp.rptq_weight_bytes(300, 256) == 512 * 128
+    assert rp.rptq_calibrate_workspace_bytes(768) == 768 * 16
+    for off in ([0, 5, 40, 100], [0, 1, 2, 3, 700], [0, 33]):
+        assert rp.rptq_padded_k(off) == packfmt.padded_layout(off)[1]
+
+
+def test_validation_happens_before_any_device_work(lib):
+    with pytest.raises(rp.RptqError) as e:
+        rp.rptq_padded_k([0, 5, 5, 9])                          # not strictly increasing
+    assert e.value.status == -5
+    with pytest.raises(rp.RptqError) as e:
+        rp.rptq_padded_k([1, 5])
+    assert e.value.status == -5
+    with pytest.raises(rp.RptqError) as e:
+        rp.rptq_padded_k(list(range(0, 66 * 4, 4)))             # 65 clusters
+    assert e.value.status == -2
+    # NULL pointers and bad bits are refused by the entry points themselves
+    i32, vp = ctypes.c_int32, ctypes.c_void_p
+    off = (i32 * 2)(0, 64)
+    one = (ctypes.c_float * 1)(1.0)
+    zero = (i32 * 1)(0)
+    dummy = vp(4096)
+    assert lib.rptq_ln_quant(None, 4, 64, None, None, 1e-5, 0, dummy, off, 1, one, one, zero, 4, dummy, None, None, None) == -1
+    assert lib.rptq_ln_quant(dummy, 4, 64, None, None, 1e-5, 0, dummy, off, 1, one, one, zero, 5, dummy, None, None, None) == -3
+    assert lib.rptq_ln_quant(dummy, 4, 72, None, None, 1e-5, 0, dummy, off, 1, one, one, zero, 4, dummy, None, None, None) == -2
+    assert lib.rptq_ln_quant(vp(4100), 4, 64, None, None, 1e-5, 0, dummy, off, 1, one, one, zero, 4, dummy, None, None, None) == -4
+    big = (i32 * 1)(1 << 22)
+    assert lib.rptq_ln_quant(dummy, 4, 64, None, None, 1e-5, 0, dummy, off, 1, one, one, big, 4, dummy, None, None, None) == -6
+    assert lib.rptq_cluster_gemm(dummy, 4, 4, dummy, 8, off, 1, one, dummy, dummy, dummy, None, dummy, 1, None) == -1
+    assert lib.rptq_cluster_gemm(dummy, 4, 4, dummy, 0, off, 1, one, dummy, dummy, dummy, dummy, dummy, 1, None) == -2
+    perm = (i32 * 4)(0, 1, 1, 3)
+    off4 = (i32 * 2)(0, 4)
+    assert lib.rptq_fold_reorder(None, None, 4, dummy, perm, off4, 1, None, None, None, 0, 0, 4, None,
+                                 dummy, None, None, None, None, None, None, None, None) == -5
+    assert b"permutation" in lib.rptq_strerror(-5)
+
+
+@pytest.mark.parametrize("cfg,g,bits,seed", [(0, 8, 8, 1), (0, 16, 4, 2), (0, 32, 3, 3), (0, 1, 4, 0)])
+def test_host_clustering_matches_oracle(cfg, g, bits, seed):
+    c = w.CONFIGS[cfg]
+    s = w.make_site(w.site_seed(cfg, 0), c.sites[0].d, 8, c.n_cal)
+    cmin, cmax = o.calibrate_minmax(s.cal, s.gamma, s.beta)
+    raw, _, _ = o.kmeans(cmin, cmax, g, seed)
+    assign, ge = o.canonical_labels(raw)
+    perm, off = o.reorder_index(assign, ge)
+    ss, inv, z, _, _ = o.cluster_params(cmin, cmax, perm, off, bits)
+    r = rp.rptq_cluster_channels(cmin, cmax, g, bits, seed)
+    assert r["g_eff"] == ge
+    for key, ref in (("assign", assign), ("perm", perm), ("cluster_off", off), ("s", ss), ("inv_s", inv), ("z", z)):
+        assert np.array_equal(r[key], ref), key
+
+
+def test_host_clustering_degenerate_points():
+    cmin = np.array([0, 0, 0, 1, 1, 1, 0, 1], dtype=np.float32)
+    cmax = np.array([2, 2, 2, 5, 5, 5, 2, 5], dtype=np.float32)
+    r = rp.rptq_cluster_channels(cmin, cmax, 4, 4, 3)
+    raw, _, _ = o.kmeans(cmin, cmax, 4, 3)
+    assign, ge = o.canonical_labels(raw)
+    assert r["g_eff"] == ge == 2 and np.array_equal(r["assign"], assign)
+
+
+@pytest.mark.parametrize("bits", [3, 4, 8])
+def test_packed_code_codec_round_trip(bits):
+    rng = np.random.default_rng(bits)
+    off = np.array([0, 5, 70, 71, 200])
+    lo, hi = o.code_range(bits)
+    codes = rng.integers(lo, hi + 1, (7, 200))
+    packed = packfmt.pack_codes(codes, off, bits)
+    assert packed.shape == (7, rp.rptq_codes_bytes(7, rp.rptq_padded_k(off), bits) // 7)
+    back, pads = packfmt.unpack_codes(packed, off, bits)
+    assert np.array_equal(back, codes) and (pads == 0).all()
+
+
+def test_packed_weight_codec_round_trip():
+    rng = np.random.default_rng(0)
+    off = np.array([0, 31, 64, 130])
+    wq = rng.integers(-8, 8, (70, 130))
+    packed = packfmt.pack_weights(wq, off)
+    assert packed.size == rp.rptq_weight_bytes(70, rp.rptq_padded_k(off))
+    back, extra = packfmt.unpack_weights(packed, 70, off)
+    assert np.array_equal(back, wq) and (extra == 0).all()
