@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the RPTQ hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input for the chosen
+workload: for every quantization site, LayerNorm-in-cluster-order + per-cluster
+quantization (one kernel), then the cluster-wise integer GEMM of every linear layer that
+reads the site.  Inputs are resident in HBM before the timed region.  Prints one JSON
+line: tokens/s of the whole step, the roofline record of the dominant kernel (measured
+with HIP events around its launches on the launch stream), and the CPU oracle timed on
+the host cores on the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+EPS = 1e-5
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: OPT-1.3b layer)")
+    ap.add_argument("--sets", type=int, default=4, help="distinct input/weight copies cycled through the steps")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2304_01089_amd as rp
+    import workloads as w
+
+    rp.load_library()                       # no fallback: the HIP library must be built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = w.CONFIGS[args.config]
+    M, bits = cfg.M, cfg.bits
+
+    def dev_bf16(x):
+        return torch.from_numpy(w.bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+    # ---- setup (untimed): synthetic inputs, calibration, folding -----------------------------
+    t_setup = time.time()
+    sites = []
+    host_sites = []
+    for si, spec in enumerate(cfg.sites):
+        if not spec.layernorm:
+            raise SystemExit("bench.py: config %d chains a ReLU site; not a bench workload yet" % args.config)
+        seed = w.site_seed(args.config, si)
+        site = w.make_site(seed, spec.d, M, cfg.n_cal)
+        gamma, beta = torch.from_numpy(site.gamma).cuda(), torch.from_numpy(site.beta).cuda()
+        cal = rp.calibrate_site([dev_bf16(b) for b in site.cal], gamma, beta, EPS, False, spec.g, bits, seed=seed)
+        xs = [dev_bf16(site.x)]
+        for k in range(1, args.sets):       # further batches from the same channel model
+            xs.append(dev_bf16(w.extra_batch(site, k, M)))
+        lins = []
+        host_W = []
+        for li, (lname, N) in enumerate(spec.gemms):
+            Wh = w.weight_matrix(seed + 500 + li, N, spec.d)
+            lin0 = rp.fold_linear(cal, torch.from_numpy(Wh).cuda())
+            copies = [lin0]
+            for k in range(1, args.sets):
+                c = rp.FoldedLinear(N=N, Wq=lin0.Wq.clone(), sW=lin0.sW.clone(), zW=lin0.zW.clone(),
+                                    wsum=lin0.wsum, colterm=lin0.colterm.clone())
+                copies.append(c)
+            ys = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(min(2, args.sets))]
+            lins.append(dict(name=lname, N=N, copies=copies, ys=ys))
+            host_W.append(Wh)
+        codes = torch.empty(rp.rptq_codes_bytes(M, cal.k_padded, bits), dtype=torch.uint8, device="cuda")
+        rowterm = torch.empty(M, dtype=torch.float32, device="cuda")
+        sites.append(dict(spec=spec, cal=cal, xs=xs, lins=lins, codes=codes, rowterm=rowterm))
+        host_sites.append(dict(site=site, W=host_W))
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    def step(i, events=None):
+        k = i % args.sets
+        for si, s in enumerate(sites):
+            cal = s["cal"]
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True); e0.record()
+            rp.rptq_ln_quant(s["xs"][k], M, cal.d, cal.gamma_pad, cal.beta_pad, EPS, False, cal.perm_pad,
+                             cal.cluster_off, cal.s, cal.inv_s, cal.z, bits, s["codes"], None, s["rowterm"])
+            if events is not None:
+                e1 = torch.cuda.Event(enable_timing=True); e1.record()
+                events.append(("ln_quant:%s" % s["spec"].name, e0, e1))
+            for lin in s["lins"]:
+                c = lin["copies"][k]
+                y = lin["ys"][i % len(lin["ys"])]
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True); e0.record()
+                rp.rptq_cluster_gemm(s["codes"], M, bits, c.Wq, c.N, cal.cluster_off, cal.s, c.sW, c.zW, c.colterm,
+                                     s["rowterm"], y)
+                if events is not None:
+                    e1 = torch.cuda.Event(enable_timing=True); e1.record()
+                    events.append(("gemm:%s" % lin["name"], e0, e1))
+
+    # ---- whole-step throughput ------------------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(args.steps):
+        step(i)
+    t1.record()
+    torch.cuda.synchronize()
+    ms_per_step = t0.elapsed_time(t1) / args.steps
+    tokens_per_s = M / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations over the same K steps (HIP events around each launch) ------------
+    events = []
+    for i in range(args.steps):
+        step(i, events)
+    torch.cuda.synchronize()
+    stage_ms = {}
+    for name, e0, e1 in events:
+        stage_ms.setdefault(name, []).append(e0.elapsed_time(e1))
+    stage_avg = {k: float(np.mean(v)) for k, v in stage_ms.items()}
+
+    # ---- roofline of the dominant kernel ---------------------------------------------------------
+    stage_info = {}
+    for s in sites:
+        d = s["spec"].d
+        name = "ln_quant:%s" % s["spec"].name
+        alg_bytes = M * (2 * d + d * bits / 8.0)
+        stage_info[name] = dict(bound="hbm", work=alg_bytes, unit="GB/s", peak=PEAK_HBM_GBS, scale=1e-9)
+        for lin in s["lins"]:
+            ops = 2.0 * M * lin["N"] * d
+            stage_info["gemm:%s" % lin["name"]] = dict(bound="mfma", work=ops, unit="TOP/s", peak=PEAK_INT8_TOPS, scale=1e-12)
+    dominant = max(stage_avg, key=lambda k: stage_avg[k])
+    info = stage_info[dominant]
+    achieved = info["work"] / (stage_avg[dominant] * 1e-3) * info["scale"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("config%d" % args.config, {}).get(dominant)
+        except Exception:
+            traffic = None
+    roofline = dict(kernel=dominant, bound=info["bound"], achieved=round(achieved, 3), peak=info["peak"],
+                    unit=info["unit"], frac=round(achieved / info["peak"], 4), traffic=traffic,
+                    avg_launch_ms=round(stage_avg[dominant], 5))
+    stages = {}
+    for k, ms in stage_avg.items():
+        si = stage_info[k]
+        ach = si["work"] / (ms * 1e-3) * si["scale"]
+        stages[k] = dict(ms=round(ms, 5), ms_median=round(float(np.median(stage_ms[k])), 5),
+                         ms_max=round(float(np.max(stage_ms[k])), 5), bound=si["bound"], achieved=round(ach, 3),
+                         unit=si["unit"], frac=round(ach / si["peak"], 4))
+
+    # ---- CPU oracle on the host cores (reported baseline) -----------------------------------------
+    cpu = None
+    if not args.no_cpu:
+        from oracle import rptq_oracle as o
+        cores = len(os.sched_getaffinity(0))
+        rows = M
+        budget_flops = 4e11                       # keeps the leg to roughly 10-30 s of CPU work
+        flops_per_row = sum(2.0 * N * s["spec"].d for s in sites for (_, N) in s["spec"].gemms)
+        rows = int(max(16, min(M, budget_flops // flops_per_row)))
+        wqs = [[o.quantize_weights(Wh, s["cal"].perm) for Wh in hs["W"]]          # offline work, untimed
+               for s, hs in zip(sites, host_sites)]
+        tc = time.perf_counter()
+        for s, hs, wl in zip(sites, host_sites, wqs):
+            cal = s["cal"]
+            codes, xsum, _ = o.ln_quant(hs["site"].x[:rows], hs["site"].gamma, hs["site"].beta, EPS, False,
+                                        cal.perm, cal.cluster_off, cal.inv_s, cal.z, bits)
+            for wq, sW, _, zW in wl:
+                o.cluster_gemm_int(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+        online = max(time.perf_counter() - tc, 1e-9)
+        cpu = dict(value=round(rows / online, 2), unit="tokens/s", cores=cores, kind="oracle",
+                   sample="%d of %d tokens, all sites and GEMMs of the workload, numpy float64/int64 oracle "
+                          "(offline weight quantization excluded)" % (rows, M), seconds=round(online, 3))
+
+    out = {
+        "metric": "tokens/s for LN+quant+cluster-GEMM per layer; % HBM GB/s or int8 MFMA peak",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "configs[%d]: %s, M=%d, A%d, sites=%s" % (
+            args.config, cfg.name, M, bits,
+            ";".join("%s(d=%d,g=%d)->%s" % (s.name, s.d, s.g, ",".join("%s %dx%d" % (n, N, s.d) for n, N in s.gemms))
+                     for s in cfg.sites)),
+            "input_sets": args.sets, "y_dtype": "bf16", "setup_s": round(t_setup, 2)},
+        "roofline": roofline,
+        "stages": stages,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -14,6 +14,7 @@ from .synth import (  # noqa: F401
     round_to_bf16,
     site_seed,
     make_site,
+    extra_batch,
     weight_rows,
     weight_matrix,
     tiny_site,

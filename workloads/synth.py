@@ -146,6 +146,12 @@ def make_site(seed: int, d: int, M: int, n_cal: int, cal_rows: int = CAL_ROWS) -
     return Site(d, m_c, s_c, gamma, beta, cal, x, seed)
 
 
+def extra_batch(site: Site, k: int, rows: int) -> np.ndarray:
+    """A further batch of `rows` tokens from the site's channel model (noise stream k >= 1)."""
+    rng = np.random.Generator(np.random.PCG64([site.seed, 7919, k]))
+    return _draw_rows(rng, site.m_c, site.s_c, rows)
+
+
 def weight_rows(seed: int, N: int, K: int, rows: np.ndarray) -> np.ndarray:
     """Selected rows of the seeded weight matrix W[N,K] (fp32), any order."""
     rows = np.asarray(rows, dtype=np.int64)
