@@ -10,6 +10,8 @@
 // are applied once at the end from per-row and per-column vectors.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "device_common.h"
 #include "rptq_internal.h"
 
@@ -26,6 +28,7 @@ struct GemmArgs {
   int32_t N;
   int32_t slices;            // K_p / 32
   int32_t used_slices;       // slices up to the end of the last cluster
+  int32_t tiles_m, tiles_n;  // output tiles along M and N
   const float* sW;
   const int32_t* zW;
   const float* colterm;
@@ -79,7 +82,7 @@ __device__ __forceinline__ void unpack3(uint32_t x0, uint32_t x1, uint32_t x2, u
 }
 
 template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, bool YF32>
-__global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab tab) {
+__global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTab tab) {
   constexpr int BM = WGM * WM * 32;
   constexpr int BN = WGN * WN * 32;
   constexpr int A_SLICE = 2 * BM * 16 + kSlicePad;       // [half][row][16 B]
@@ -101,74 +104,76 @@ __global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab t
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int64_t m0 = static_cast<int64_t>(blockIdx.y) * BM;
-  const int n0 = blockIdx.x * BN;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
+  // contiguous band of output columns, all row tiles of one column tile back to back.
+  const int tiles_m = a.tiles_m, tiles_n = a.tiles_n;
+  const int total = tiles_m * tiles_n;
+  int lin = blockIdx.x;
+  if (total % 8 == 0) lin = (lin & 7) * (total >> 3) + (lin >> 3);
+  const int64_t m0 = static_cast<int64_t>(lin % tiles_m) * BM;
+  const int n0 = (lin / tiles_m) * BN;
 
   // ---- global -> register staging ------------------------------------------------------
-  uint32_t ra[A_PER][A_REGS];
-  uint4 rb[B_PER];
+  uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run two K steps ahead
+  uint4 rb[2][B_PER];
   const uint8_t* a_ptr[A_PER];
   const uint8_t* b_ptr[B_PER];
   int a_lds[A_PER], b_lds[B_PER];
 #pragma unroll
   for (int i = 0; i < A_PER; ++i) {
-    const int unit = tid + i * 256;
+    // surplus threads repeat a valid unit (same bytes to the same LDS address): no divergent
+    // branches around the loads, so all of a step's loads are in flight together
+    const int unit = (tid + i * 256) % A_UNITS;
     const int row = unit / kStepSlices, s = unit % kStepSlices;
     int64_t grow = m0 + row;
     if (grow >= a.M) grow = a.M - 1;                       // clamp: loads stay in bounds, rows never stored
     a_ptr[i] = a.codes + grow * a.row_bytes + s * GB;
     a_lds[i] = s * A_SLICE + row * 16;
-    if (unit >= A_UNITS) a_lds[i] = -1;
   }
 #pragma unroll
   for (int i = 0; i < B_PER; ++i) {
-    const int unit = tid + i * 256;
+    const int unit = (tid + i * 256) % B_UNITS;
     const int blk = unit / 32, p = unit % 32;
     const int rbl = blk / kStepSlices, s = blk % kStepSlices;
     b_ptr[i] = a.Wq + ((static_cast<size_t>(n0 / 32 + rbl) * a.slices + s) * 64) * 8 + p * 16;
     const int h = p / 16, r = (2 * p) % 32;
     b_lds[i] = s * B_SLICE + h * (BN * 16) + (rbl * 32 + r) * 16;
-    if (unit >= B_UNITS) b_lds[i] = -1;
   }
 
-  auto load_global = [&](int step) {
+  auto load_global = [&](int step, int q) {
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
-      if (a_lds[i] < 0) continue;
       const uint32_t* p = reinterpret_cast<const uint32_t*>(a_ptr[i] + static_cast<size_t>(step) * kStepSlices * GB);
 #pragma unroll
-      for (int k = 0; k < A_REGS; ++k) ra[i][k] = p[k];
+      for (int k = 0; k < A_REGS; ++k) ra[q][i][k] = p[k];
     }
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
-      if (b_lds[i] < 0) continue;
-      rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + static_cast<size_t>(step) * kStepSlices * 512);
+      rb[q][i] = *reinterpret_cast<const uint4*>(b_ptr[i] + static_cast<size_t>(step) * kStepSlices * 512);
     }
   };
 
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&](int buf, int q) {
     unsigned char* dA = sA + buf * A_STAGE;
     unsigned char* dB = sB + buf * B_STAGE;
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
-      if (a_lds[i] < 0) continue;
       uint4 lo, hi;
       if (BITS == 8) {
-        lo = make_uint4(ra[i][0], ra[i][1], ra[i][2], ra[i][3]);
-        hi = make_uint4(ra[i][4 % A_REGS], ra[i][5 % A_REGS], ra[i][6 % A_REGS], ra[i][7 % A_REGS]);
+        lo = make_uint4(ra[q][i][0], ra[q][i][1], ra[q][i][2], ra[q][i][3]);
+        hi = make_uint4(ra[q][i][4 % A_REGS], ra[q][i][5 % A_REGS], ra[q][i][6 % A_REGS], ra[q][i][7 % A_REGS]);
       } else if (BITS == 4) {
-        unpack4(make_uint4(ra[i][0], ra[i][1], ra[i][2], ra[i][3]), &lo, &hi);
+        unpack4(make_uint4(ra[q][i][0], ra[q][i][1], ra[q][i][2], ra[q][i][3]), &lo, &hi);
       } else {
-        unpack3(ra[i][0], ra[i][1], ra[i][2], &lo, &hi);
+        unpack3(ra[q][i][0], ra[q][i][1], ra[q][i][2], &lo, &hi);
       }
       *reinterpret_cast<uint4*>(dA + a_lds[i]) = lo;
       *reinterpret_cast<uint4*>(dA + a_lds[i] + BM * 16) = hi;
     }
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
-      if (b_lds[i] < 0) continue;
       uint4 r0, r1;                                        // rows r and r+1 of the same k half
-      unpack4(rb[i], &r0, &r1);
+      unpack4(rb[q][i], &r0, &r1);
       *reinterpret_cast<uint4*>(dB + b_lds[i]) = r0;
       *reinterpret_cast<uint4*>(dB + b_lds[i] + 16) = r1;
     }
@@ -192,28 +197,45 @@ __global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab t
   const int b_frag = (lane >> 5) * (BN * 16) + (wn * WN * 32 + (lane & 31)) * 16;
 
   int ci = 0;
+  bool fresh = true;
   int next_end = tab.slice_end[0];
   const int steps = (a.used_slices + kStepSlices - 1) / kStepSlices;
 
-  load_global(0);
-  for (int step = 0; step < steps; ++step) {
-    const int buf = step & 1;
-    store_lds(buf);
+  load_global(0, 0);
+  if (steps > 1) load_global(1, 1);
+  auto k_step = [&](int step, auto parity) {
+    constexpr int buf = decltype(parity)::value;            // LDS stage and staging set of this step
+    store_lds(buf, buf);
     __syncthreads();
-    if (step + 1 < steps) load_global(step + 1);
+    if (step + 2 < steps) load_global(step + 2, buf);
     const unsigned char* cA = sA + buf * A_STAGE;
     const unsigned char* cB = sB + buf * B_STAGE;
+    v4i fa[2][WM], fb[2][WN];                               // operand fragments, one slice ahead
+    auto load_frags = [&](int s, int q) {
+#pragma unroll
+      for (int i = 0; i < WM; ++i) fa[q][i] = *reinterpret_cast<const v4i*>(cA + s * A_SLICE + a_frag + i * 32 * 16);
+#pragma unroll
+      for (int j = 0; j < WN; ++j) fb[q][j] = *reinterpret_cast<const v4i*>(cB + s * B_SLICE + b_frag + j * 32 * 16);
+    };
+    load_frags(0, 0);
 #pragma unroll
     for (int s = 0; s < kStepSlices; ++s) {
-      v4i fa[WM], fb[WN];
+      if (s + 1 < kStepSlices) load_frags(s + 1, (s + 1) & 1);
+      if (fresh) {                                           // first slice of a cluster: C = 0, nothing to clear
+        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < WM; ++i) fa[i] = *reinterpret_cast<const v4i*>(cA + s * A_SLICE + a_frag + i * 32 * 16);
+        for (int i = 0; i < WM; ++i)
 #pragma unroll
-      for (int j = 0; j < WN; ++j) fb[j] = *reinterpret_cast<const v4i*>(cB + s * B_SLICE + b_frag + j * 32 * 16);
+          for (int j = 0; j < WN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], zero, 0, 0, 0);
+        fresh = false;
+      } else {
 #pragma unroll
-      for (int i = 0; i < WM; ++i)
+        for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < WN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
+      }
 
       const int gs = step * kStepSlices + s + 1;           // slices accumulated so far
       if (gs == next_end) {                                  // cluster ci is complete (uniform branch)
@@ -224,10 +246,10 @@ __global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab t
           for (int i = 0; i < WM; ++i)
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
-              const int n = n0 + (wn * WN + j) * 32 + (lane & 31);
+              const int64_t t = m0 + (wm * WM + i) * 32 + (lane & 31);
 #pragma unroll
               for (int r = 0; r < 16; ++r) {
-                const int64_t t = m0 + (wm * WM + i) * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
+                const int n = n0 + (wn * WN + j) * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
                 if (t < a.M && n < a.N) {
                   const int p = acc[i][j][r] >> (ActFmt<BITS>::kShift + 4);
                   const int zw = a.zW[n];
@@ -235,7 +257,6 @@ __global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab t
                                 zw * a.xsum[t * tab.g + ci] + nn * zx * zw;
                   a.yq[(static_cast<int64_t>(ci) * a.M + t) * a.N + n] = v;
                 }
-                acc[i][j][r] = 0;
               }
             }
         } else {
@@ -244,39 +265,91 @@ __global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab t
 #pragma unroll
             for (int j = 0; j < WN; ++j)
 #pragma unroll
-              for (int r = 0; r < 16; ++r) {
+              for (int r = 0; r < 16; ++r)
                 facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
-                acc[i][j][r] = 0;
-              }
         }
+        fresh = true;
         ++ci;
         next_end = ci < tab.g ? tab.slice_end[ci] : -1;
       }
     }
+  };
+  for (int step = 0; step < steps; step += 2) {
+    k_step(step, std::integral_constant<int, 0>());
+    if (step + 1 < steps) k_step(step + 1, std::integral_constant<int, 1>());
   }
 
-  // ---- zero-point terms and output scale ---------------------------------------------------
+  // ---- zero-point terms, output scale, store ----------------------------------------------------
+  // D[n][t]: a lane holds one token (lane & 31) and, per register quad, four consecutive output
+  // channels.  Results go through a wave-private LDS tile in row-major [token][channel] order and
+  // leave as 16-byte stores that cover whole rows of the tile.
   if (!PARTIALS) {
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    constexpr int ES = YF32 ? 4 : 2;
+    constexpr int TROWS = WM * 32, TCOLS = WN * 32;
+    constexpr int PITCH = TCOLS * ES + 16;                 // bytes; the pad spreads rows over banks
+    __syncthreads();                                        // every wave is done with the pipeline buffers
+    unsigned char* tile = smem + wave * (TROWS * PITCH);
+    const int nw0 = n0 + wn * TCOLS;                        // first output channel of this wave
+    const bool vec_ok = (a.N % 8) == 0;
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      const int n = n0 + (wn * WN + j) * 32 + (lane & 31);
-      const bool n_ok = n < a.N;
-      const float sw = n_ok ? a.sW[n] : 0.0f;
-      const float ct = n_ok ? a.colterm[n] : 0.0f;
-      const float zw = n_ok ? static_cast<float>(a.zW[n]) : 0.0f;
+    for (int i = 0; i < WM; ++i) {
+      int64_t t = m0 + (wm * WM + i) * 32 + (lane & 31);
+      t = t < a.M ? t : a.M - 1;
+      const float rt = a.rowterm[t];
 #pragma unroll
-      for (int i = 0; i < WM; ++i) {
+      for (int j = 0; j < WN; ++j) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int64_t t = m0 + (wm * WM + i) * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
-          if (t < a.M && n_ok) {
-            const float v = sw * ((facc[i][j][r] - ct) - zw * a.rowterm[t]);
-            if (YF32) {
-              static_cast<float*>(a.y)[t * a.N + n] = v;
-            } else {
-              const uint32_t bits = __float_as_uint(v);
-              const uint32_t rounded = bits + 0x7fffu + ((bits >> 16) & 1u);   // round to nearest even
-              static_cast<uint16_t*>(a.y)[t * a.N + n] = static_cast<uint16_t>(rounded >> 16);
+        for (int q = 0; q < 4; ++q) {
+          const int nl = j * 32 + q * 8 + (lane >> 5) * 4;  // four consecutive channels nl..nl+3
+          float sw[4], ct[4], zw[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            int n = nw0 + nl + e;
+            n = n < a.N ? n : a.N - 1;
+            sw[e] = a.sW[n];
+            ct[e] = a.colterm[n];
+            zw[e] = static_cast<float>(a.zW[n]);
+          }
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = sw[e] * ((facc[i][j][q * 4 + e] - ct[e]) - zw[e] * rt);
+          unsigned char* dst = tile + (i * 32 + (lane & 31)) * PITCH + nl * ES;
+          if (YF32) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            const f2 p0 = {v[0], v[1]}, p1 = {v[2], v[3]};
+            const b2 c0 = __builtin_convertvector(p0, b2), c1 = __builtin_convertvector(p1, b2);   // round to nearest even
+            uint2 o;
+            o.x = *reinterpret_cast<const uint32_t*>(&c0);
+            o.y = *reinterpret_cast<const uint32_t*>(&c1);
+            *reinterpret_cast<uint2*>(dst) = o;
+          }
+        }
+      }
+    }
+    // the tile is private to the wave: its own LDS writes are visible to it in program order
+    constexpr int LANES_PER_ROW = TCOLS * ES / 16;
+    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+    const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
+    unsigned char* ybase = static_cast<unsigned char*>(a.y);
+#pragma unroll
+    for (int pass = 0; pass < TROWS / ROWS_PER_PASS; ++pass) {
+      const int row = pass * ROWS_PER_PASS + rr;
+      const int64_t t = m0 + wm * TROWS + row;
+      const int n = nw0 + cc * (16 / ES);
+      const uint4 val = *reinterpret_cast<const uint4*>(tile + row * PITCH + cc * 16);
+      if (t < a.M) {
+        if (vec_ok && n + (16 / ES) <= a.N) {
+          *reinterpret_cast<uint4*>(ybase + (t * a.N + n) * ES) = val;
+        } else {
+          const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+          for (int e = 0; e < 16 / ES; ++e) {
+            if (n + e < a.N) {
+              if (YF32) reinterpret_cast<uint32_t*>(ybase)[t * a.N + n + e] = w[e];
+              else reinterpret_cast<uint16_t*>(ybase)[t * a.N + n + e] = static_cast<uint16_t>(w[e / 2] >> (16 * (e & 1)));
             }
           }
         }
@@ -289,11 +362,16 @@ __global__ void __launch_bounds__(256) cluster_gemm_kernel(GemmArgs a, GemmTab t
 template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, bool YF32>
 static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st) {
   constexpr int BM = WGM * WM * 32, BN = WGN * WN * 32;
-  constexpr size_t shmem = 2 * kStepSlices * ((2 * BM * 16 + kSlicePad) + (2 * BN * 16 + kSlicePad));
+  constexpr size_t pipe = 2 * kStepSlices * ((2 * BM * 16 + kSlicePad) + (2 * BN * 16 + kSlicePad));
+  constexpr size_t stage = PARTIALS ? 0 : 4 * (WM * 32) * (WN * 32 * (YF32 ? 4 : 2) + 16);   // output tiles, one per wave
+  constexpr size_t shmem = pipe > stage ? pipe : stage;
   auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, YF32>;
   if (shmem > 64 * 1024) RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
-  const dim3 grid((a.N + BN - 1) / BN, static_cast<unsigned>((a.M + BM - 1) / BM));
-  hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, a, tab);
+  GemmArgs b = a;
+  b.tiles_n = (a.N + BN - 1) / BN;
+  b.tiles_m = static_cast<int32_t>((a.M + BM - 1) / BM);
+  const dim3 grid(static_cast<unsigned>(b.tiles_n) * static_cast<unsigned>(b.tiles_m));
+  hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab);
   RPTQ_HIP(hipGetLastError());
   return RPTQ_OK;
 }
