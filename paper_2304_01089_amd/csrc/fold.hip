@@ -31,8 +31,8 @@ __global__ void fold_ln_kernel(const float* gamma, const float* beta, const int3
 // Byte offset of the dword holding padded columns 8u..8u+7 of output row o.
 __device__ __host__ __forceinline__ size_t weight_dword_offset(int o, int u, int k_padded) {
   const int rb = o >> 5, r = o & 31;
-  const int s = u >> 2, k8 = u & 3, h = k8 >> 1, v = k8 & 1;
-  return ((static_cast<size_t>(rb) * (k_padded / kGroup) + s) * 64 + h * 32 + r) * 8 + v * 4;
+  const int kb = u >> 4, s = (u >> 2) & 3, k8 = u & 3, h = k8 >> 1, v = k8 & 1;
+  return ((static_cast<size_t>(rb) * (k_padded / RPTQ_K_ALIGN) + kb) * 64 + h * 32 + r) * 32 + s * 8 + v * 4;
 }
 
 struct FoldArgs {

@@ -1,13 +1,15 @@
 // Cluster-wise integer product (App. A.4, second method) on int8 MFMA.
 //
 // K runs over the padded cluster-order layout in slices of 32 codes, so a cluster always
-// ends on a slice boundary.  Packed 3/4/8-bit activation codes and packed 4-bit weight
-// codes are loaded from global memory, turned into sign-carrying int8 (code << 5, << 4 or
-// << 0; weights << 4) with one shift/mask per four codes, and written to LDS in the order
-// the 32x32x32 int8 MFMA reads its operands.  When the last slice of cluster i has been
-// accumulated, the int32 accumulators hold 2^shift * P_i; they are converted, scaled by
-// sX_i / 2^shift, added to the fp32 result and cleared.  The zero-point terms of App. A.4
-// are applied once at the end from per-row and per-column vectors.
+// ends on a slice boundary.  Activation codes (3/4/8 bit, packed) go global -> registers ->
+// int8 in LDS (code << 5, << 4 or << 0, one shift/mask per four codes) in the order the
+// 32x32x32 int8 MFMA reads its operand.  Weight codes (4 bit, packed in MFMA-lane order) go
+// global -> registers and are expanded to int8 (code << 4) in registers right before use:
+// they never touch LDS, which would otherwise be the bandwidth limit of this kernel.
+// When the last slice of cluster i has been accumulated, the int32 accumulators hold
+// 2^shift * P_i; they are converted, scaled by sX_i / 2^shift and added to the fp32 result.
+// The zero-point terms of App. A.4 are applied once at the end from per-row and per-column
+// vectors.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -49,7 +51,8 @@ struct GemmTab {
 };
 
 constexpr int kStepSlices = 4;            // slices per K step (128 codes)
-constexpr int kSlicePad = 32;             // bytes added to a slice's LDS stride (bank spread on writes)
+constexpr int kSlicePad = 64;             // bytes added to a slice's LDS stride: 16 banks, so the four
+                                          // slices a 16-lane write group touches fall in distinct banks
 
 template <int BITS>
 struct ActFmt {
@@ -86,19 +89,14 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   constexpr int BM = WGM * WM * 32;
   constexpr int BN = WGN * WN * 32;
   constexpr int A_SLICE = 2 * BM * 16 + kSlicePad;       // [half][row][16 B]
-  constexpr int B_SLICE = 2 * BN * 16 + kSlicePad;
   constexpr int A_STAGE = kStepSlices * A_SLICE;
-  constexpr int B_STAGE = kStepSlices * B_SLICE;
   constexpr int A_UNITS = BM * kStepSlices;              // (row, slice) units per K step
-  constexpr int B_UNITS = (BN / 32) * kStepSlices * 32;  // 16-byte units per K step
   constexpr int A_PER = (A_UNITS + 255) / 256;
-  constexpr int B_PER = (B_UNITS + 255) / 256;
   constexpr int GB = ActFmt<BITS>::kGroupBytes;
   constexpr int A_REGS = GB / 4;                          // dwords per A unit
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* sA = smem;                               // [2][A_STAGE]
-  unsigned char* sB = smem + 2 * A_STAGE;                 // [2][B_STAGE]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -114,11 +112,11 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   const int n0 = (lin / tiles_m) * BN;
 
   // ---- global -> register staging ------------------------------------------------------
-  uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run two K steps ahead
-  uint4 rb[2][B_PER];
+  uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run ahead of use
+  uint4 wreg[2][WN][2];                                   // this lane's weight bytes: [set][block][slices 0-1 | 2-3]
   const uint8_t* a_ptr[A_PER];
-  const uint8_t* b_ptr[B_PER];
-  int a_lds[A_PER], b_lds[B_PER];
+  const uint8_t* w_ptr[WN];
+  int a_lds[A_PER];
 #pragma unroll
   for (int i = 0; i < A_PER; ++i) {
     // surplus threads repeat a valid unit (same bytes to the same LDS address): no divergent
@@ -130,53 +128,49 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     a_ptr[i] = a.codes + grow * a.row_bytes + s * GB;
     a_lds[i] = s * A_SLICE + row * 16;
   }
+  const int ksteps = a.slices / kStepSlices;
 #pragma unroll
-  for (int i = 0; i < B_PER; ++i) {
-    const int unit = (tid + i * 256) % B_UNITS;
-    const int blk = unit / 32, p = unit % 32;
-    const int rbl = blk / kStepSlices, s = blk % kStepSlices;
-    b_ptr[i] = a.Wq + ((static_cast<size_t>(n0 / 32 + rbl) * a.slices + s) * 64) * 8 + p * 16;
-    const int h = p / 16, r = (2 * p) % 32;
-    b_lds[i] = s * B_SLICE + h * (BN * 16) + (rbl * 32 + r) * 16;
-  }
+  for (int j = 0; j < WN; ++j)
+    w_ptr[j] = a.Wq + (static_cast<size_t>(n0 / 32 + wn * WN + j) * ksteps * 64 + lane) * 32;
 
-  auto load_global = [&](int step, int q) {
+  auto load_a = [&](int step, int q) {
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
       const uint32_t* p = reinterpret_cast<const uint32_t*>(a_ptr[i] + static_cast<size_t>(step) * kStepSlices * GB);
 #pragma unroll
       for (int k = 0; k < A_REGS; ++k) ra[q][i][k] = p[k];
     }
+  };
+  auto load_w = [&](int step, int q) {
 #pragma unroll
-    for (int i = 0; i < B_PER; ++i) {
-      rb[q][i] = *reinterpret_cast<const uint4*>(b_ptr[i] + static_cast<size_t>(step) * kStepSlices * 512);
+    for (int j = 0; j < WN; ++j) {
+      const uint4* p = reinterpret_cast<const uint4*>(w_ptr[j] + static_cast<size_t>(step) * 2048);
+      wreg[q][j][0] = p[0];
+      wreg[q][j][1] = p[1];
     }
   };
 
-  auto store_lds = [&](int buf, int q) {
+  // unpack one half (16 codes) of a staged unit to int8 and write it to LDS stage `buf`
+  auto store_a_half = [&](int buf, int q, int i, int half) {
     unsigned char* dA = sA + buf * A_STAGE;
-    unsigned char* dB = sB + buf * B_STAGE;
-#pragma unroll
-    for (int i = 0; i < A_PER; ++i) {
-      uint4 lo, hi;
-      if (BITS == 8) {
-        lo = make_uint4(ra[q][i][0], ra[q][i][1], ra[q][i][2], ra[q][i][3]);
-        hi = make_uint4(ra[q][i][4 % A_REGS], ra[q][i][5 % A_REGS], ra[q][i][6 % A_REGS], ra[q][i][7 % A_REGS]);
-      } else if (BITS == 4) {
-        unpack4(make_uint4(ra[q][i][0], ra[q][i][1], ra[q][i][2], ra[q][i][3]), &lo, &hi);
+    uint4 v;
+    if (BITS == 8) {
+      v = half ? make_uint4(ra[q][i][4 % A_REGS], ra[q][i][5 % A_REGS], ra[q][i][6 % A_REGS], ra[q][i][7 % A_REGS])
+               : make_uint4(ra[q][i][0], ra[q][i][1], ra[q][i][2], ra[q][i][3]);
+    } else if (BITS == 4) {
+      const uint32_t x = ra[q][i][half * 2], y = ra[q][i][half * 2 + 1];
+      v = make_uint4(x & 0xf0f0f0f0u, (x << 4) & 0xf0f0f0f0u, y & 0xf0f0f0f0u, (y << 4) & 0xf0f0f0f0u);
+    } else {
+      const uint32_t x0 = ra[q][i][0], x1 = ra[q][i][1], x2 = ra[q][i][2];
+      if (half == 0) {
+        v = make_uint4(x0 & 0xe0e0e0e0u, (x0 << 3) & 0xe0e0e0e0u, x1 & 0xe0e0e0e0u, (x1 << 3) & 0xe0e0e0e0u);
       } else {
-        unpack3(ra[q][i][0], ra[q][i][1], ra[q][i][2], &lo, &hi);
+        v = make_uint4(x2 & 0xe0e0e0e0u, (x2 << 3) & 0xe0e0e0e0u,
+                       ((x0 << 6) & 0xc0c0c0c0u) | ((x2 << 5) & 0x20202020u),
+                       ((x1 << 6) & 0xc0c0c0c0u) | ((x2 << 4) & 0x20202020u));
       }
-      *reinterpret_cast<uint4*>(dA + a_lds[i]) = lo;
-      *reinterpret_cast<uint4*>(dA + a_lds[i] + BM * 16) = hi;
     }
-#pragma unroll
-    for (int i = 0; i < B_PER; ++i) {
-      uint4 r0, r1;                                        // rows r and r+1 of the same k half
-      unpack4(rb[q][i], &r0, &r1);
-      *reinterpret_cast<uint4*>(dB + b_lds[i]) = r0;
-      *reinterpret_cast<uint4*>(dB + b_lds[i] + 16) = r1;
-    }
+    *reinterpret_cast<uint4*>(dA + a_lds[i] + half * (BM * 16)) = v;
   };
 
   // ---- accumulators -----------------------------------------------------------------------
@@ -194,47 +188,92 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     }
 
   const int a_frag = (lane >> 5) * (BM * 16) + (wm * WM * 32 + (lane & 31)) * 16;
-  const int b_frag = (lane >> 5) * (BN * 16) + (wn * WN * 32 + (lane & 31)) * 16;
 
   int ci = 0;
   bool fresh = true;
   int next_end = tab.slice_end[0];
   const int steps = (a.used_slices + kStepSlices - 1) / kStepSlices;
 
-  load_global(0, 0);
-  if (steps > 1) load_global(1, 1);
+  // Pipeline.  Activations: LDS holds two stages; while stage p feeds the MFMAs of K step
+  // `step`, the registers loaded earlier are unpacked into stage p^1 between those MFMAs, and
+  // the loads of step+3 are issued after the step's single barrier.  Weights: register set p
+  // feeds step `step`; it is refilled with step+2 as soon as the step is done.
+  load_a(0, 0);
+  load_w(0, 0);
+  if (steps > 1) { load_a(1, 1); load_w(1, 1); }
+#pragma unroll
+  for (int u = 0; u < A_PER; ++u) {
+    store_a_half(0, 0, u, 0);
+    store_a_half(0, 0, u, 1);
+  }
+  __syncthreads();
+  if (steps > 2) load_a(2, 0);
+
+  v4i fb[2][WN];                                            // weight fragments (code << 4), one slice ahead
+  auto unpack_w = [&](int q, int set, int s, int j) {       // fb[q][j] <- slice s of weight set `set`
+    const uint4 w = wreg[set][j][s >> 1];
+    const uint32_t x = (s & 1) ? w.z : w.x, y = (s & 1) ? w.w : w.y;
+    fb[q][j][0] = static_cast<int>(x & 0xf0f0f0f0u);
+    fb[q][j][1] = static_cast<int>((x << 4) & 0xf0f0f0f0u);
+    fb[q][j][2] = static_cast<int>(y & 0xf0f0f0f0u);
+    fb[q][j][3] = static_cast<int>((y << 4) & 0xf0f0f0f0u);
+  };
+#pragma unroll
+  for (int j = 0; j < WN; ++j) unpack_w(0, 0, 0, j);
+
   auto k_step = [&](int step, auto parity) {
-    constexpr int buf = decltype(parity)::value;            // LDS stage and staging set of this step
-    store_lds(buf, buf);
-    __syncthreads();
-    if (step + 2 < steps) load_global(step + 2, buf);
+    constexpr int buf = decltype(parity)::value;            // LDS stage / weight set read by this step
     const unsigned char* cA = sA + buf * A_STAGE;
-    const unsigned char* cB = sB + buf * B_STAGE;
-    v4i fa[2][WM], fb[2][WN];                               // operand fragments, one slice ahead
+    v4i fa[2][WM];                                          // activation fragments, one slice ahead
     auto load_frags = [&](int s, int q) {
 #pragma unroll
       for (int i = 0; i < WM; ++i) fa[q][i] = *reinterpret_cast<const v4i*>(cA + s * A_SLICE + a_frag + i * 32 * 16);
-#pragma unroll
-      for (int j = 0; j < WN; ++j) fb[q][j] = *reinterpret_cast<const v4i*>(cB + s * B_SLICE + b_frag + j * 32 * 16);
     };
     load_frags(0, 0);
-#pragma unroll
-    for (int s = 0; s < kStepSlices; ++s) {
-      if (s + 1 < kStepSlices) load_frags(s + 1, (s + 1) & 1);
-      if (fresh) {                                           // first slice of a cluster: C = 0, nothing to clear
+    auto do_slice = [&](auto s_tag) {
+      constexpr int s = decltype(s_tag)::value;
+      // One basic block per slice: the MFMAs of this slice with, between them, everything else
+      // that is due - next slice's activation fragments (LDS reads), next slice's weight
+      // fragments (register unpack) and a share of the next stage's activation unpack + LDS
+      // write - so that the matrix pipe never waits for a burst of other instructions.
+      auto slice_body = [&](auto fresh_tag) {
+        constexpr bool kFresh = decltype(fresh_tag)::value;
+        constexpr int NM = WM * WN;
+        constexpr int n_units = (A_PER > s) ? (A_PER - s + kStepSlices - 1) / kStepSlices : 0;   // units u with u % 4 == s
+        constexpr int NP = WN + 2 * n_units;
+        if (s + 1 < kStepSlices) load_frags(s + 1, (s + 1) & 1);
+        auto piece = [&](int k) {
+          if (k < WN) {
+            // (on the last step the "next" data is stale and its results are never used)
+            if (s + 1 < kStepSlices) unpack_w((s + 1) & 1, buf, s + 1, k);
+            else unpack_w(0, buf ^ 1, 0, k);
+          } else {
+            const int h = k - WN;
+            store_a_half(buf ^ 1, buf ^ 1, s + (h >> 1) * kStepSlices, h & 1);
+          }
+        };
         const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < WM; ++i)
+        for (int m = 0; m < NM; ++m) {
+          const int i = m / WN, j = m % WN;
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], kFresh ? zero : acc[i][j], 0, 0, 0);
 #pragma unroll
-          for (int j = 0; j < WN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], zero, 0, 0, 0);
+          for (int k = m; k < NP; k += NM) piece(k);
+        }
+        // pin the order: LDS reads first, then one MFMA followed by its share of the rest
+        __builtin_amdgcn_sched_group_barrier(0x100, WM, 0);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+          __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+      };
+      if (fresh) {                                           // first slice of a cluster: C = 0, nothing to clear
+        slice_body(std::true_type());
         fresh = false;
       } else {
-#pragma unroll
-        for (int i = 0; i < WM; ++i)
-#pragma unroll
-          for (int j = 0; j < WN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
+        slice_body(std::false_type());
       }
 
       const int gs = step * kStepSlices + s + 1;           // slices accumulated so far
@@ -272,7 +311,15 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
         ++ci;
         next_end = ci < tab.g ? tab.slice_end[ci] : -1;
       }
-    }
+    };
+    do_slice(std::integral_constant<int, 0>());
+    do_slice(std::integral_constant<int, 1>());
+    do_slice(std::integral_constant<int, 2>());
+    do_slice(std::integral_constant<int, 3>());
+    static_assert(kStepSlices == 4, "four slices per K step");
+    if (step + 2 < steps) load_w(step + 2, buf);
+    __syncthreads();
+    if (step + 3 < steps) load_a(step + 3, buf ^ 1);
   };
   for (int step = 0; step < steps; step += 2) {
     k_step(step, std::integral_constant<int, 0>());
@@ -362,7 +409,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, bool YF32>
 static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st) {
   constexpr int BM = WGM * WM * 32, BN = WGN * WN * 32;
-  constexpr size_t pipe = 2 * kStepSlices * ((2 * BM * 16 + kSlicePad) + (2 * BN * 16 + kSlicePad));
+  constexpr size_t pipe = 2 * kStepSlices * (2 * BM * 16 + kSlicePad);
   constexpr size_t stage = PARTIALS ? 0 : 4 * (WM * 32) * (WN * 32 * (YF32 ? 4 : 2) + 16);   // output tiles, one per wave
   constexpr size_t shmem = pipe > stage ? pipe : stage;
   auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, YF32>;
