@@ -45,7 +45,7 @@ struct GemmArgs {
 struct GemmTab {
   int32_t g;
   int32_t slice_end[RPTQ_MAX_CLUSTERS];   // first slice after cluster i
-  float scale[RPTQ_MAX_CLUSTERS];         // sX_i / 2^shift
+  float scale[RPTQ_MAX_CLUSTERS];         // (sX_i - sX_{i+1}) / 2^shift
   int32_t zx[RPTQ_MAX_CLUSTERS];
   int32_t n[RPTQ_MAX_CLUSTERS];           // channels in cluster i
 };
@@ -175,6 +175,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   // ---- accumulators -----------------------------------------------------------------------
   v16i acc[WM][WN];
+  v16i prev[PARTIALS ? WM : 1][PARTIALS ? WN : 1];          // verification mode: running sum at the last boundary
   float facc[PARTIALS ? 1 : WM][PARTIALS ? 1 : WN][16];
 #pragma unroll
   for (int i = 0; i < WM; ++i)
@@ -183,6 +184,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         acc[i][j][r] = 0;
+        if (PARTIALS) prev[i][j][r] = 0;
         if (!PARTIALS) facc[i][j][r] = 0.0f;
       }
     }
@@ -190,7 +192,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   const int a_frag = (lane >> 5) * (BM * 16) + (wm * WM * 32 + (lane & 31)) * 16;
 
   int ci = 0;
-  bool fresh = true;
   int next_end = tab.slice_end[0];
   const int steps = (a.used_slices + kStepSlices - 1) / kStepSlices;
 
@@ -236,8 +237,10 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       // that is due - next slice's activation fragments (LDS reads), next slice's weight
       // fragments (register unpack) and a share of the next stage's activation unpack + LDS
       // write - so that the matrix pipe never waits for a burst of other instructions.
-      auto slice_body = [&](auto fresh_tag) {
-        constexpr bool kFresh = decltype(fresh_tag)::value;
+      // The int32 accumulators are never cleared: they hold the running sum C_i over clusters
+      // 1..i, and sum_i sX_i P_i = sum_i (sX_i - sX_{i+1}) C_i (sX_{g+1} = 0), so a cluster
+      // boundary costs one convert and one fma per accumulator and no branch in the MFMA code.
+      {
         constexpr int NM = WM * WN;
         constexpr int n_units = (A_PER > s) ? (A_PER - s + kStepSlices - 1) / kStepSlices : 0;   // units u with u % 4 == s
         constexpr int NP = WN + 2 * n_units;
@@ -252,11 +255,10 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
             store_a_half(buf ^ 1, buf ^ 1, s + (h >> 1) * kStepSlices, h & 1);
           }
         };
-        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
           const int i = m / WN, j = m % WN;
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], kFresh ? zero : acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
 #pragma unroll
           for (int k = m; k < NP; k += NM) piece(k);
         }
@@ -268,12 +270,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
           __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
           __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
         }
-      };
-      if (fresh) {                                           // first slice of a cluster: C = 0, nothing to clear
-        slice_body(std::true_type());
-        fresh = false;
-      } else {
-        slice_body(std::false_type());
       }
 
       const int gs = step * kStepSlices + s + 1;           // slices accumulated so far
@@ -290,12 +286,13 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
               for (int r = 0; r < 16; ++r) {
                 const int n = n0 + (wn * WN + j) * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
                 if (t < a.M && n < a.N) {
-                  const int p = acc[i][j][r] >> (ActFmt<BITS>::kShift + 4);
+                  const int p = (acc[i][j][r] - prev[i][j][r]) >> (ActFmt<BITS>::kShift + 4);
                   const int zw = a.zW[n];
                   const int v = p - zx * a.wsum[static_cast<int64_t>(n) * tab.g + ci] -
                                 zw * a.xsum[t * tab.g + ci] + nn * zx * zw;
                   a.yq[(static_cast<int64_t>(ci) * a.M + t) * a.N + n] = v;
                 }
+                prev[i][j][r] = acc[i][j][r];
               }
             }
         } else {
@@ -307,7 +304,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
               for (int r = 0; r < 16; ++r)
                 facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
         }
-        fresh = true;
         ++ci;
         next_end = ci < tab.g ? tab.slice_end[ci] : -1;
       }
@@ -328,76 +324,80 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   // ---- zero-point terms, output scale, store ----------------------------------------------------
   // D[n][t]: a lane holds one token (lane & 31) and, per register quad, four consecutive output
-  // channels.  Results go through a wave-private LDS tile in row-major [token][channel] order and
-  // leave as 16-byte stores that cover whole rows of the tile.
+  // channels.  The fp32 sums go through an LDS tile of the whole workgroup in row-major
+  // [token][channel] order; afterwards every thread owns a fixed group of channels (its
+  // per-channel constants are loaded once), finishes the arithmetic and writes 16 bytes per
+  // row, so that rows of the output tile leave as full cache lines.
   if (!PARTIALS) {
     typedef float f2 __attribute__((ext_vector_type(2)));
     typedef __bf16 b2 __attribute__((ext_vector_type(2)));
-    constexpr int ES = YF32 ? 4 : 2;
-    constexpr int TROWS = WM * 32, TCOLS = WN * 32;
-    constexpr int PITCH = TCOLS * ES + 16;                 // bytes; the pad spreads rows over banks
+    constexpr int TP = BN + 4;                              // tile pitch in floats (16-byte pad: rows spread over banks)
+    float* tile = reinterpret_cast<float*>(smem);
     __syncthreads();                                        // every wave is done with the pipeline buffers
-    unsigned char* tile = smem + wave * (TROWS * PITCH);
-    const int nw0 = n0 + wn * TCOLS;                        // first output channel of this wave
-    const bool vec_ok = (a.N % 8) == 0;
 #pragma unroll
-    for (int i = 0; i < WM; ++i) {
-      int64_t t = m0 + (wm * WM + i) * 32 + (lane & 31);
-      t = t < a.M ? t : a.M - 1;
-      const float rt = a.rowterm[t];
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-      for (int j = 0; j < WN; ++j) {
+      for (int j = 0; j < WN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int nl = j * 32 + q * 8 + (lane >> 5) * 4;  // four consecutive channels nl..nl+3
-          float sw[4], ct[4], zw[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            int n = nw0 + nl + e;
-            n = n < a.N ? n : a.N - 1;
-            sw[e] = a.sW[n];
-            ct[e] = a.colterm[n];
-            zw[e] = static_cast<float>(a.zW[n]);
-          }
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = sw[e] * ((facc[i][j][q * 4 + e] - ct[e]) - zw[e] * rt);
-          unsigned char* dst = tile + (i * 32 + (lane & 31)) * PITCH + nl * ES;
-          if (YF32) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            const f2 p0 = {v[0], v[1]}, p1 = {v[2], v[3]};
-            const b2 c0 = __builtin_convertvector(p0, b2), c1 = __builtin_convertvector(p1, b2);   // round to nearest even
-            uint2 o;
-            o.x = *reinterpret_cast<const uint32_t*>(&c0);
-            o.y = *reinterpret_cast<const uint32_t*>(&c1);
-            *reinterpret_cast<uint2*>(dst) = o;
-          }
+          const int tl = (wm * WM + i) * 32 + (lane & 31);
+          const int nl = (wn * WN + j) * 32 + q * 8 + (lane >> 5) * 4;
+          *reinterpret_cast<float4*>(tile + tl * TP + nl) =
+              make_float4(facc[i][j][q * 4 + 0], facc[i][j][q * 4 + 1], facc[i][j][q * 4 + 2], facc[i][j][q * 4 + 3]);
         }
-      }
+    __syncthreads();
+    constexpr int CW = YF32 ? 4 : 8;                        // outputs per 16-byte store
+    constexpr int CPR = BN / CW;                            // chunks per tile row
+    constexpr int RPP = 256 / CPR;                          // tile rows per pass
+    static_assert(256 % CPR == 0 && BM % RPP == 0, "output tiling");
+    const int cc = tid % CPR, rr = tid / CPR;
+    const int n = n0 + cc * CW;
+    float sw[CW], ct[CW], zw[CW];
+#pragma unroll
+    for (int e = 0; e < CW; ++e) {
+      const int nc = (n + e) < a.N ? (n + e) : a.N - 1;     // clamped: always in bounds
+      sw[e] = a.sW[nc];
+      ct[e] = a.colterm[nc];
+      zw[e] = static_cast<float>(a.zW[nc]);
     }
-    // the tile is private to the wave: its own LDS writes are visible to it in program order
-    constexpr int LANES_PER_ROW = TCOLS * ES / 16;
-    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
-    const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
+    const bool vec_ok = (a.N % 8) == 0 && n + CW <= a.N;
     unsigned char* ybase = static_cast<unsigned char*>(a.y);
+#pragma unroll 4
+    for (int pass = 0; pass < BM / RPP; ++pass) {
+      const int row = pass * RPP + rr;
+      const int64_t t = m0 + row;
+      const float rt = a.rowterm[t < a.M ? t : a.M - 1];
+      float v[CW];
 #pragma unroll
-    for (int pass = 0; pass < TROWS / ROWS_PER_PASS; ++pass) {
-      const int row = pass * ROWS_PER_PASS + rr;
-      const int64_t t = m0 + wm * TROWS + row;
-      const int n = nw0 + cc * (16 / ES);
-      const uint4 val = *reinterpret_cast<const uint4*>(tile + row * PITCH + cc * 16);
+      for (int e4 = 0; e4 < CW / 4; ++e4) {
+        const float4 f = *reinterpret_cast<const float4*>(tile + row * TP + cc * CW + e4 * 4);
+        v[e4 * 4 + 0] = f.x; v[e4 * 4 + 1] = f.y; v[e4 * 4 + 2] = f.z; v[e4 * 4 + 3] = f.w;
+      }
+#pragma unroll
+      for (int e = 0; e < CW; ++e) v[e] = sw[e] * ((v[e] - ct[e]) - zw[e] * rt);
       if (t < a.M) {
-        if (vec_ok && n + (16 / ES) <= a.N) {
-          *reinterpret_cast<uint4*>(ybase + (t * a.N + n) * ES) = val;
-        } else {
-          const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+        if (YF32) {
+          if (vec_ok) {
+            *reinterpret_cast<float4*>(ybase + (t * a.N + n) * 4) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
 #pragma unroll
-          for (int e = 0; e < 16 / ES; ++e) {
-            if (n + e < a.N) {
-              if (YF32) reinterpret_cast<uint32_t*>(ybase)[t * a.N + n + e] = w[e];
-              else reinterpret_cast<uint16_t*>(ybase)[t * a.N + n + e] = static_cast<uint16_t>(w[e / 2] >> (16 * (e & 1)));
-            }
+            for (int e = 0; e < CW; ++e)
+              if (n + e < a.N) reinterpret_cast<float*>(ybase)[t * a.N + n + e] = v[e];
+          }
+        } else {
+          uint32_t w[CW / 2];
+#pragma unroll
+          for (int e = 0; e < CW / 2; ++e) {
+            const f2 pr = {v[2 * e], v[2 * e + 1]};
+            const b2 cv = __builtin_convertvector(pr, b2);   // round to nearest even
+            w[e] = *reinterpret_cast<const uint32_t*>(&cv);
+          }
+          if (vec_ok) {
+            *reinterpret_cast<uint4*>(ybase + (t * a.N + n) * 2) = make_uint4(w[0], w[1 % (CW / 2)], w[2 % (CW / 2)], w[3 % (CW / 2)]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < CW; ++e)
+              if (n + e < a.N) reinterpret_cast<uint16_t*>(ybase)[t * a.N + n + e] = static_cast<uint16_t>(w[e / 2] >> (16 * (e & 1)));
           }
         }
       }
@@ -410,7 +410,7 @@ template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, bool YF32>
 static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st) {
   constexpr int BM = WGM * WM * 32, BN = WGN * WN * 32;
   constexpr size_t pipe = 2 * kStepSlices * (2 * BM * 16 + kSlicePad);
-  constexpr size_t stage = PARTIALS ? 0 : 4 * (WM * 32) * (WN * 32 * (YF32 ? 4 : 2) + 16);   // output tiles, one per wave
+  constexpr size_t stage = PARTIALS ? 0 : static_cast<size_t>(BM) * (BN + 4) * 4;   // fp32 output tile of the workgroup
   constexpr size_t shmem = pipe > stage ? pipe : stage;
   auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, YF32>;
   if (shmem > 64 * 1024) RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
@@ -426,7 +426,9 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st)
 template <int BITS, bool PARTIALS, bool YF32>
 static int32_t launch_shape(const GemmArgs& a, const GemmTab& tab, hipStream_t st) {
   if (a.M <= 32) return launch_cfg<BITS, 1, 4, 1, 1, PARTIALS, YF32>(a, tab, st);
-  return launch_cfg<BITS, 2, 2, 2, 2, PARTIALS, YF32>(a, tab, st);
+  // 128 x 128 tile; every wave covers all 128 tokens and 32 output channels: each expanded
+  // weight fragment feeds four MFMAs and no two waves expand the same weights
+  return launch_cfg<BITS, 1, 4, 4, 1, PARTIALS, YF32>(a, tab, st);
 }
 
 template <int BITS>
@@ -463,7 +465,10 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
   for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i) {
     const bool in = i < geom.g;
     tab.slice_end[i] = in ? geom.pad_off[i + 1] / kGroup : -1;
-    tab.scale[i] = (in && sX) ? sX[i] / static_cast<float>(1 << shift) : 0.0f;
+    // difference of consecutive cluster scales (the accumulators hold running sums)
+    const double s_here = (in && sX) ? static_cast<double>(sX[i]) : 0.0;
+    const double s_next = (i + 1 < geom.g && sX) ? static_cast<double>(sX[i + 1]) : 0.0;
+    tab.scale[i] = static_cast<float>((s_here - s_next) / static_cast<double>(1 << shift));
     tab.zx[i] = (in && zX) ? zX[i] : 0;
     tab.n[i] = in ? geom.off[i + 1] - geom.off[i] : 0;
   }
