@@ -23,7 +23,7 @@
  * Padded cluster-order layout ("K_p")
  *    Cluster i with n_i = cluster_off[i+1]-cluster_off[i] channels occupies
  *    pad32(n_i) consecutive positions; the total is rounded up to a multiple of
- *    RPTQ_K_ALIGN (128).  Pad positions hold activation code 0 and weight code 0 and
+ *    RPTQ_K_ALIGN (256).  Pad positions hold activation code 0 and weight code 0 and
  *    never contribute.  rptq_padded_k() returns K_p.
  *
  * Packed activation codes: row-major, one row = K_p/32 groups of 32 codes.
@@ -55,7 +55,7 @@ extern "C" {
 #endif
 
 #define RPTQ_MAX_CLUSTERS 64
-#define RPTQ_K_ALIGN 128
+#define RPTQ_K_ALIGN 256
 #define RPTQ_N_ALIGN 256
 #define RPTQ_MAX_CHANNELS 32768
 

@@ -38,6 +38,8 @@ class RptqError(RuntimeError):
 
 
 def library_path() -> str:
+    if os.environ.get("RPTQ_LIBRARY"):          # an alternative build of the same library
+        return os.environ["RPTQ_LIBRARY"]
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "librptq.so")
 
 

@@ -31,7 +31,8 @@ def hipcc() -> str:
 
 def _compile(src: str, objdir: str, verbose: bool) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), "-x", "hip", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("RPTQ_EXTRA_FLAGS", "").split()
+    cmd = [hipcc(), "-x", "hip", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, res.stdout, res.stderr))
@@ -48,13 +49,14 @@ def build_library(verbose: bool = False, jobs: int = 6) -> str:
     os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(lambda s: _compile(s, objdir, verbose), SOURCES))
-    tmp = LIB + ".tmp"
+    lib = os.environ.get("RPTQ_LIBRARY_OUT", LIB)
+    tmp = lib + ".tmp"
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (res.stdout, res.stderr))
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -50,7 +50,7 @@ struct GemmTab {
   int32_t n[RPTQ_MAX_CLUSTERS];           // channels in cluster i
 };
 
-constexpr int kStepSlices = 4;            // slices per K step (128 codes)
+constexpr int kStepSlices = 8;            // slices per K step (256 codes): one barrier per step
 constexpr int kSlicePad = 64;             // bytes added to a slice's LDS stride: 16 banks, so the four
                                           // slices a 16-lane write group touches fall in distinct banks
 
@@ -113,7 +113,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   // ---- global -> register staging ------------------------------------------------------
   uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run ahead of use
-  uint4 wreg[2][WN][2];                                   // this lane's weight bytes: [set][block][slices 0-1 | 2-3]
+  uint4 wreg[2][WN][kStepSlices / 2];                     // this lane's weight bytes: [set][block][slice pair]
   const uint8_t* a_ptr[A_PER];
   const uint8_t* w_ptr[WN];
   int a_lds[A_PER];
@@ -128,10 +128,10 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     a_ptr[i] = a.codes + grow * a.row_bytes + s * GB;
     a_lds[i] = s * A_SLICE + row * 16;
   }
-  const int ksteps = a.slices / kStepSlices;
+  const int wblocks = a.slices / (kWBlockCols / kGroup);   // packed weight blocks per 32-row band
 #pragma unroll
   for (int j = 0; j < WN; ++j)
-    w_ptr[j] = a.Wq + (static_cast<size_t>(n0 / 32 + wn * WN + j) * ksteps * 64 + lane) * 32;
+    w_ptr[j] = a.Wq + (static_cast<size_t>(n0 / 32 + wn * WN + j) * wblocks * 64 + lane) * 32;
 
   auto load_a = [&](int step, int q) {
 #pragma unroll
@@ -144,9 +144,12 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   auto load_w = [&](int step, int q) {
 #pragma unroll
     for (int j = 0; j < WN; ++j) {
-      const uint4* p = reinterpret_cast<const uint4*>(w_ptr[j] + static_cast<size_t>(step) * 2048);
-      wreg[q][j][0] = p[0];
-      wreg[q][j][1] = p[1];
+#pragma unroll
+      for (int b = 0; b < kStepSlices / 4; ++b) {           // one 2 KiB weight block per four slices
+        const uint4* p = reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + b) * 2048);
+        wreg[q][j][2 * b] = p[0];
+        wreg[q][j][2 * b + 1] = p[1];
+      }
     }
   };
 
@@ -242,8 +245,10 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       // boundary costs one convert and one fma per accumulator and no branch in the MFMA code.
       {
         constexpr int NM = WM * WN;
-        constexpr int n_units = (A_PER > s) ? (A_PER - s + kStepSlices - 1) / kStepSlices : 0;   // units u with u % 4 == s
-        constexpr int NP = WN + 2 * n_units;
+        // the step's A units are spread evenly over its slices
+        constexpr int u_lo = (s * A_PER + kStepSlices - 1) / kStepSlices;          // first unit of this slice
+        constexpr int u_hi = ((s + 1) * A_PER + kStepSlices - 1) / kStepSlices;    // one past its last unit
+        constexpr int NP = WN + 2 * (u_hi - u_lo);
         if (s + 1 < kStepSlices) load_frags(s + 1, (s + 1) & 1);
         auto piece = [&](int k) {
           if (k < WN) {
@@ -252,7 +257,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
             else unpack_w(0, buf ^ 1, 0, k);
           } else {
             const int h = k - WN;
-            store_a_half(buf ^ 1, buf ^ 1, s + (h >> 1) * kStepSlices, h & 1);
+            store_a_half(buf ^ 1, buf ^ 1, u_lo + (h >> 1), h & 1);
           }
         };
 #pragma unroll
@@ -312,7 +317,11 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     do_slice(std::integral_constant<int, 1>());
     do_slice(std::integral_constant<int, 2>());
     do_slice(std::integral_constant<int, 3>());
-    static_assert(kStepSlices == 4, "four slices per K step");
+    do_slice(std::integral_constant<int, 4>());
+    do_slice(std::integral_constant<int, 5>());
+    do_slice(std::integral_constant<int, 6>());
+    do_slice(std::integral_constant<int, 7>());
+    static_assert(kStepSlices == 8, "eight slices per K step");
     if (step + 2 < steps) load_w(step + 2, buf);
     __syncthreads();
     if (step + 3 < steps) load_a(step + 3, buf ^ 1);
@@ -332,7 +341,29 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     typedef float f2 __attribute__((ext_vector_type(2)));
     typedef __bf16 b2 __attribute__((ext_vector_type(2)));
     constexpr int TP = BN + 4;                              // tile pitch in floats (16-byte pad: rows spread over banks)
+    constexpr int CW = YF32 ? 4 : 8;                        // outputs per 16-byte store
+    constexpr int CPR = BN / CW;                            // chunks per tile row
+    constexpr int RPP = 256 / CPR;                          // tile rows per pass
+    constexpr int NPASS = BM / RPP;
+    static_assert(256 % CPR == 0 && BM % RPP == 0, "output tiling");
     float* tile = reinterpret_cast<float*>(smem);
+    // per-channel and per-row terms of this thread's share: requested first, so that their
+    // latency runs under the LDS transpose
+    const int cc = tid % CPR, rr = tid / CPR;
+    const int n = n0 + cc * CW;
+    float sw[CW], ct[CW], zw[CW], rt[NPASS];
+#pragma unroll
+    for (int e = 0; e < CW; ++e) {
+      const int nc = (n + e) < a.N ? (n + e) : a.N - 1;     // clamped: always in bounds
+      sw[e] = a.sW[nc];
+      ct[e] = a.colterm[nc];
+      zw[e] = static_cast<float>(a.zW[nc]);
+    }
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int64_t t = m0 + pass * RPP + rr;
+      rt[pass] = a.rowterm[t < a.M ? t : a.M - 1];
+    }
     __syncthreads();                                        // every wave is done with the pipeline buffers
 #pragma unroll
     for (int i = 0; i < WM; ++i)
@@ -346,27 +377,12 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
               make_float4(facc[i][j][q * 4 + 0], facc[i][j][q * 4 + 1], facc[i][j][q * 4 + 2], facc[i][j][q * 4 + 3]);
         }
     __syncthreads();
-    constexpr int CW = YF32 ? 4 : 8;                        // outputs per 16-byte store
-    constexpr int CPR = BN / CW;                            // chunks per tile row
-    constexpr int RPP = 256 / CPR;                          // tile rows per pass
-    static_assert(256 % CPR == 0 && BM % RPP == 0, "output tiling");
-    const int cc = tid % CPR, rr = tid / CPR;
-    const int n = n0 + cc * CW;
-    float sw[CW], ct[CW], zw[CW];
-#pragma unroll
-    for (int e = 0; e < CW; ++e) {
-      const int nc = (n + e) < a.N ? (n + e) : a.N - 1;     // clamped: always in bounds
-      sw[e] = a.sW[nc];
-      ct[e] = a.colterm[nc];
-      zw[e] = static_cast<float>(a.zW[nc]);
-    }
     const bool vec_ok = (a.N % 8) == 0 && n + CW <= a.N;
     unsigned char* ybase = static_cast<unsigned char*>(a.y);
-#pragma unroll 4
-    for (int pass = 0; pass < BM / RPP; ++pass) {
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
       const int row = pass * RPP + rr;
       const int64_t t = m0 + row;
-      const float rt = a.rowterm[t < a.M ? t : a.M - 1];
       float v[CW];
 #pragma unroll
       for (int e4 = 0; e4 < CW / 4; ++e4) {
@@ -374,7 +390,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
         v[e4 * 4 + 0] = f.x; v[e4 * 4 + 1] = f.y; v[e4 * 4 + 2] = f.z; v[e4 * 4 + 3] = f.w;
       }
 #pragma unroll
-      for (int e = 0; e < CW; ++e) v[e] = sw[e] * ((v[e] - ct[e]) - zw[e] * rt);
+      for (int e = 0; e < CW; ++e) v[e] = sw[e] * ((v[e] - ct[e]) - zw[e] * rt[pass]);
       if (t < a.M) {
         if (YF32) {
           if (vec_ok) {
@@ -428,7 +444,7 @@ static int32_t launch_shape(const GemmArgs& a, const GemmTab& tab, hipStream_t s
   if (a.M <= 32) return launch_cfg<BITS, 1, 4, 1, 1, PARTIALS, YF32>(a, tab, st);
   // 128 x 128 tile; every wave covers all 128 tokens and 32 output channels: each expanded
   // weight fragment feeds four MFMAs and no two waves expand the same weights
-  return launch_cfg<BITS, 1, 4, 4, 1, PARTIALS, YF32>(a, tab, st);
+  return launch_cfg<BITS, 1, 4, 2, 2, PARTIALS, YF32>(a, tab, st);
 }
 
 template <int BITS>

@@ -9,6 +9,7 @@
 namespace rptq {
 
 constexpr int kGroup = 32;                 // codes per packed group; cluster padding unit
+constexpr int kWBlockCols = 128;           // columns of one packed weight block (32 rows x 128 columns = 2 KiB)
 constexpr int32_t kZLimit = 1 << 21;       // largest |zero point| the fp32 clamp bounds carry exactly
 
 // Cluster geometry passed to kernels by value (g <= RPTQ_MAX_CLUSTERS).

@@ -4,7 +4,7 @@ GEMM kernels oracle-made codes and to decode what the quantization kernels wrote
 import numpy as np
 
 GROUP = 32
-K_ALIGN = 128
+K_ALIGN = 256
 N_ALIGN = 256
 
 

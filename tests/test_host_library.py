@@ -37,7 +37,7 @@ def test_library_exports_every_declared_symbol(lib):
 
 def test_size_queries():
     assert rp.rptq_padded_k([0, 5, 40, 100]) == 256            # 32 + 64 + 64 = 160 -> 256
-    assert rp.rptq_padded_k([0, 128]) == 128
+    assert rp.rptq_padded_k([0, 128]) == 256
     assert rp.rptq_padded_k([0, 129]) == 256
     assert rp.rptq_codes_bytes(10, 256, 4) == 10 * 128
     assert rp.rptq_codes_bytes(10, 256, 3) == 10 * 96
