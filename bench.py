@@ -133,14 +133,22 @@ def main():
     tokens_per_s = M / (ms_per_step * 1e-3)
 
     # ---- per-kernel durations over the same K steps (HIP events around each launch) ------------
+    import gc
     events = []
+    gc.disable()
     for i in range(args.steps):
         step(i, events)
     torch.cuda.synchronize()
+    gc.enable()
     stage_ms = {}
     for name, e0, e1 in events:
         stage_ms.setdefault(name, []).append(e0.elapsed_time(e1))
-    stage_avg = {k: float(np.mean(v)) for k, v in stage_ms.items()}
+    # An event pair also spans any host-side stall between its two records (the launch sits
+    # between them); such samples are far outside the kernel's duration and are dropped.
+    def robust_mean(v):
+        v = np.asarray(v, dtype=np.float64)
+        return float(v[v <= 3.0 * np.median(v)].mean())
+    stage_avg = {k: robust_mean(v) for k, v in stage_ms.items()}
 
     # ---- roofline of the dominant kernel ---------------------------------------------------------
     stage_info = {}
