@@ -28,4 +28,4 @@ from .binding import (  # noqa: F401
     DTYPE_BF16,
     DTYPE_F32,
 )
-from .layer import Calibration, FoldedLinear, calibrate_site, fold_linear, ln_quant, cluster_gemm  # noqa: F401
+from .layer import Calibration, FoldedLinear, calibrate_site, identity_site, fold_linear, ln_quant, cluster_gemm  # noqa: F401

@@ -57,6 +57,24 @@ def calibrate_site(x_batches, gamma, beta, eps, relu, g, bits, seed=0, max_iter=
     return cal
 
 
+def identity_site(cal: Calibration) -> Calibration:
+    """The same site for an input that already arrives in its cluster order (the output of a
+    linear layer whose rows were permuted offline by this site's reorder index): the gather
+    is the identity; clusters, parameters and padding are unchanged.  No LayerNorm."""
+    import copy
+    import torch
+    out = copy.copy(cal)
+    ident = np.arange(cal.d, dtype=np.int32)
+    out.perm = ident
+    out.perm_dev = torch.from_numpy(ident).to(cal.perm_dev.device)
+    out.perm_pad = torch.empty_like(cal.perm_pad)
+    out.gamma_pad = None
+    out.beta_pad = None
+    B.rptq_fold_reorder(None, None, cal.d, out.perm_dev, ident, cal.cluster_off, None, None, None, 0, cal.d, None,
+                        out.perm_pad, None, None, None, None, None, None, None)
+    return out
+
+
 def fold_linear(cal: Calibration, W, perm_out=None) -> FoldedLinear:
     import torch
     N, K = W.shape
