@@ -34,7 +34,7 @@ __global__ void minmax_final_kernel(const uint32_t* keys, int d, float* ch_min, 
 template <bool LN>
 __global__ void __launch_bounds__(1024) minmax_kernel(const uint4* x, int64_t rows, int d, const float* gamma,
                                                       const float* beta, float eps, int relu, uint32_t* keys) {
-  __shared__ double red[2][kMaxWaves][2];
+  __shared__ double red[2][2][kMaxWaves];
   const int tid = threadIdx.x, T = blockDim.x, lane = tid & 63, wid = tid >> 6, nw = T >> 6;
   const int chunks = d / 8;
 
@@ -75,15 +75,12 @@ __global__ void __launch_bounds__(1024) minmax_kernel(const uint4* x, int64_t ro
     if (LN) {
       const double r1 = wave_sum(s1), r2 = wave_sum(s2);
       if (lane == 0) {
-        red[parity][wid][0] = r1;
-        red[parity][wid][1] = r2;
+        red[parity][0][wid] = r1;
+        red[parity][1][wid] = r2;
       }
       __syncthreads();
-      double t1 = 0.0, t2 = 0.0;
-      for (int w = 0; w < nw; ++w) {
-        t1 += red[parity][w][0];
-        t2 += red[parity][w][1];
-      }
+      const double t1 = partials_sum(red[parity][0], nw, lane);
+      const double t2 = partials_sum(red[parity][1], nw, lane);
       row_stats(t1, t2, d, eps, &mu, &rstd);
     }
 #pragma unroll

@@ -11,10 +11,45 @@ constexpr int kMaxWaves = 16;   // 1024 threads
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+// ---- cross-lane sums on the DPP path (no LDS round trips) -------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double v) {
+  const uint32_t lo = static_cast<uint32_t>(__double_as_longlong(v));
+  const uint32_t hi = static_cast<uint32_t>(__double_as_longlong(v) >> 32);
+  // lanes outside ROW_MASK (or without a source) receive 0.0
+  const uint32_t plo = __builtin_amdgcn_update_dpp(0u, lo, CTRL, ROW_MASK, 0xf, false);
+  const uint32_t phi = __builtin_amdgcn_update_dpp(0u, hi, CTRL, ROW_MASK, 0xf, false);
+  return v + __longlong_as_double(static_cast<long long>((static_cast<uint64_t>(phi) << 32) | plo));
+}
+
+// Sum over the 16 lanes of each DPP row; every lane of the row ends with the row's sum.
+__device__ __forceinline__ double row16_sum(double v) {
+  v = dpp_add<0xB1, 0xf>(v);     // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xf>(v);     // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xf>(v);    // row_half_mirror
+  v = dpp_add<0x140, 0xf>(v);    // row_mirror
   return v;
+}
+
+__device__ __forceinline__ double read_lane(double v, int lane) {
+  const uint32_t lo = __builtin_amdgcn_readlane(static_cast<uint32_t>(__double_as_longlong(v)), lane);
+  const uint32_t hi = __builtin_amdgcn_readlane(static_cast<uint32_t>(__double_as_longlong(v) >> 32), lane);
+  return __longlong_as_double(static_cast<long long>((static_cast<uint64_t>(hi) << 32) | lo));
+}
+
+// Sum over the 64 lanes of the wave in a fixed order; the result is wave-uniform.
+__device__ __forceinline__ double wave_sum(double v) {
+  v = row16_sum(v);
+  v = dpp_add<0x142, 0xa>(v);    // row_bcast15 into rows 1 and 3
+  v = dpp_add<0x143, 0xc>(v);    // row_bcast31 into rows 2 and 3
+  return read_lane(v, 63);
+}
+
+// Sum of per-wave partials p[0..nw) (nw <= 16) held in LDS, same order in every wave.
+__device__ __forceinline__ double partials_sum(const double* p, int nw, int lane) {
+  double v = (lane < nw) ? p[lane] : 0.0;
+  v = row16_sum(v);
+  return read_lane(v, 0);
 }
 
 // Row statistics of LayerNorm from exact fp64 sums of the bf16 inputs:

@@ -163,22 +163,19 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     if (next_row < a.M) load_row(next_row);
 
     // one reduction carries the row sums and the previous row's de-quantized sum
-    double* slot = red + parity * (kMaxWaves * 3);
+    double* slot = red + parity * (kMaxWaves * 3);        // [3][kMaxWaves]
     {
       const double r1 = wave_sum(s1), r2 = wave_sum(s2), r3 = wave_sum(rt_prev);
       if (lane == 0) {
-        slot[wid * 3 + 0] = r1;
-        slot[wid * 3 + 1] = r2;
-        slot[wid * 3 + 2] = r3;
+        slot[0 * kMaxWaves + wid] = r1;
+        slot[1 * kMaxWaves + wid] = r2;
+        slot[2 * kMaxWaves + wid] = r3;
       }
     }
     __syncthreads();
-    double t1 = 0.0, t2 = 0.0, t3 = 0.0;
-    for (int w = 0; w < nw; ++w) {
-      t1 += slot[w * 3 + 0];
-      t2 += slot[w * 3 + 1];
-      t3 += slot[w * 3 + 2];
-    }
+    const double t1 = partials_sum(slot + 0 * kMaxWaves, nw, lane);
+    const double t2 = partials_sum(slot + 1 * kMaxWaves, nw, lane);
+    const double t3 = partials_sum(slot + 2 * kMaxWaves, nw, lane);
     if (tid == 0 && prev_row >= 0 && a.rowterm) a.rowterm[prev_row] = static_cast<float>(t3);
     float mu = 0.0f, rstd = 1.0f;
     if (LN) row_stats(t1, t2, a.d, a.eps, &mu, &rstd);
@@ -244,13 +241,10 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   if (prev_row >= 0 && a.rowterm) {
     double* slot = red + parity * (kMaxWaves * 3);
     const double r3 = wave_sum(rt_prev);
-    if (lane == 0) slot[wid * 3 + 2] = r3;
+    if (lane == 0) slot[2 * kMaxWaves + wid] = r3;
     __syncthreads();
-    if (tid == 0) {
-      double t3 = 0.0;
-      for (int w = 0; w < nw; ++w) t3 += slot[w * 3 + 2];
-      a.rowterm[prev_row] = static_cast<float>(t3);
-    }
+    const double t3 = partials_sum(slot + 2 * kMaxWaves, nw, lane);
+    if (tid == 0) a.rowterm[prev_row] = static_cast<float>(t3);
   }
 }
 
