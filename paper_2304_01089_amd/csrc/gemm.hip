@@ -40,6 +40,7 @@ struct GemmArgs {
   const int32_t* xsum;
   const int32_t* wsum;
   int32_t* yq;
+  int32_t first_round;       // workgroups resident at once (2 per compute unit); 0 = no start offset
 };
 
 struct GemmTab {
@@ -102,6 +103,14 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
+  // The two workgroups of a compute unit would otherwise run in lockstep: both in the MFMA
+  // loop, then both in the output stage.  The second half of the first round starts a few
+  // microseconds late, so that one workgroup's stores and prologue run under the other's MFMAs;
+  // later workgroups take over a slot when it frees and inherit the offset.
+  if (static_cast<int>(blockIdx.x) < a.first_round && static_cast<int>(blockIdx.x) >= a.first_round / 2) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) __builtin_amdgcn_s_sleep(32);
+  }
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
   // contiguous band of output columns, all row tiles of one column tile back to back.
   const int tiles_m = a.tiles_m, tiles_n = a.tiles_n;
@@ -133,13 +142,18 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   for (int j = 0; j < WN; ++j)
     w_ptr[j] = a.Wq + (static_cast<size_t>(n0 / 32 + wn * WN + j) * wblocks * 64 + lane) * 32;
 
+  auto load_a_unit = [&](int step, int q, int i) {
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(a_ptr[i] + static_cast<size_t>(step) * kStepSlices * GB);
+#pragma unroll
+    for (int k = 0; k < A_REGS; ++k) ra[q][i][k] = p[k];
+  };
   auto load_a = [&](int step, int q) {
 #pragma unroll
-    for (int i = 0; i < A_PER; ++i) {
-      const uint32_t* p = reinterpret_cast<const uint32_t*>(a_ptr[i] + static_cast<size_t>(step) * kStepSlices * GB);
-#pragma unroll
-      for (int k = 0; k < A_REGS; ++k) ra[q][i][k] = p[k];
-    }
+    for (int i = 0; i < A_PER; ++i) load_a_unit(step, q, i);
+  };
+  // one slice pair (32 bytes per lane) of weight block j
+  auto load_w_pair = [&](int step, int q, int j, int pi) {
+    wreg[q][j][pi] = *reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + (pi >> 1)) * 2048 + (pi & 1) * 16);
   };
   auto load_w = [&](int step, int q) {
 #pragma unroll
@@ -194,24 +208,37 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   const int a_frag = (lane >> 5) * (BM * 16) + (wm * WM * 32 + (lane & 31)) * 16;
 
+  // cluster tables live in one register each (lane i holds cluster i): a boundary reads them
+  // with a lane read, no memory access inside the loop
+  const float tab_scale = tab.scale[lane];
+  const int tab_end = tab.slice_end[lane];
   int ci = 0;
-  int next_end = tab.slice_end[0];
+  int next_end = __builtin_amdgcn_readlane(tab_end, 0);
   const int steps = (a.used_slices + kStepSlices - 1) / kStepSlices;
 
   // Pipeline.  Activations: LDS holds two stages; while stage p feeds the MFMAs of K step
-  // `step`, the registers loaded earlier are unpacked into stage p^1 between those MFMAs, and
-  // the loads of step+3 are issued after the step's single barrier.  Weights: register set p
-  // feeds step `step`; it is refilled with step+2 as soon as the step is done.
+  // `step`, the registers loaded earlier are unpacked into stage p^1 between those MFMAs.
+  // Weights: register set p feeds step `step`.  Every staging register is refilled right after
+  // its last use - activations with the data of step+3, weights with step+2 - so each load has
+  // two full steps to arrive.
+  // (step indices are clamped to the last step instead of guarding the loads: a load that is
+  // always issued lets the compiler count outstanding loads exactly, and the surplus data of
+  // the tail is never used)
+  const int last = steps - 1;
   load_a(0, 0);
   load_w(0, 0);
-  if (steps > 1) { load_a(1, 1); load_w(1, 1); }
+  load_a(min(1, last), 1);
+  load_w(min(1, last), 1);
 #pragma unroll
   for (int u = 0; u < A_PER; ++u) {
     store_a_half(0, 0, u, 0);
     store_a_half(0, 0, u, 1);
   }
+  // every prologue load has landed before the loop starts: the loop's own waits then count
+  // only the loads of the steady state (vmcnt(0); the other counters are left alone)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
-  if (steps > 2) load_a(2, 0);
+  load_a(min(2, last), 0);
 
   v4i fb[2][WN];                                            // weight fragments (code << 4), one slice ahead
   auto unpack_w = [&](int q, int set, int s, int j) {       // fb[q][j] <- slice s of weight set `set`
@@ -234,6 +261,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       for (int i = 0; i < WM; ++i) fa[q][i] = *reinterpret_cast<const v4i*>(cA + s * A_SLICE + a_frag + i * 32 * 16);
     };
     load_frags(0, 0);
+    const int w_step = min(step + 2, last), a_step = min(step + 3, last);
     auto do_slice = [&](auto s_tag) {
       constexpr int s = decltype(s_tag)::value;
       // One basic block per slice: the MFMAs of this slice with, between them, everything else
@@ -267,6 +295,13 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 #pragma unroll
           for (int k = m; k < NP; k += NM) piece(k);
         }
+        // refill the staging registers this slice has finished with
+        if (s & 1) {
+#pragma unroll
+          for (int j = 0; j < WN; ++j) load_w_pair(w_step, buf, j, s >> 1);
+        }
+#pragma unroll
+        for (int u = u_lo; u < u_hi; ++u) load_a_unit(a_step, buf ^ 1, u);
         // pin the order: LDS reads first, then one MFMA followed by its share of the rest
         __builtin_amdgcn_sched_group_barrier(0x100, WM, 0);
 #pragma unroll
@@ -279,7 +314,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
       const int gs = step * kStepSlices + s + 1;           // slices accumulated so far
       if (gs == next_end) {                                  // cluster ci is complete (uniform branch)
-        const float sc = tab.scale[ci];
+        const float sc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, tab_scale), ci));
         if (PARTIALS) {
           const int zx = tab.zx[ci], nn = tab.n[ci];
 #pragma unroll
@@ -310,7 +345,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
                 facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
         }
         ++ci;
-        next_end = ci < tab.g ? tab.slice_end[ci] : -1;
+        next_end = __builtin_amdgcn_readlane(tab_end, ci & 63);
       }
     };
     do_slice(std::integral_constant<int, 0>());
@@ -322,14 +357,16 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     do_slice(std::integral_constant<int, 6>());
     do_slice(std::integral_constant<int, 7>());
     static_assert(kStepSlices == 8, "eight slices per K step");
-    if (step + 2 < steps) load_w(step + 2, buf);
     __syncthreads();
-    if (step + 3 < steps) load_a(step + 3, buf ^ 1);
   };
-  for (int step = 0; step < steps; step += 2) {
+  // (pairs of steps in the loop, an odd last step after it: with no branch around a step inside
+  // the loop, the count of loads in flight at the loop head is the same on every path)
+  int step = 0;
+  for (; step + 1 < steps; step += 2) {
     k_step(step, std::integral_constant<int, 0>());
-    if (step + 1 < steps) k_step(step + 1, std::integral_constant<int, 1>());
+    k_step(step + 1, std::integral_constant<int, 1>());
   }
+  if (step < steps) k_step(step, std::integral_constant<int, 0>());
 
   // ---- zero-point terms, output scale, store ----------------------------------------------------
   // D[n][t]: a lane holds one token (lane & 31) and, per register quad, four consecutive output
@@ -434,6 +471,10 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st)
   b.tiles_n = (a.N + BN - 1) / BN;
   b.tiles_m = static_cast<int32_t>((a.M + BM - 1) / BM);
   const dim3 grid(static_cast<unsigned>(b.tiles_n) * static_cast<unsigned>(b.tiles_m));
+  int dev = 0, cus = 0;
+  RPTQ_HIP(hipGetDevice(&dev));
+  RPTQ_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  b.first_round = (BM > 32 && grid.x >= 2u * static_cast<unsigned>(cus)) ? 2 * cus : 0;
   hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab);
   RPTQ_HIP(hipGetLastError());
   return RPTQ_OK;
