@@ -16,50 +16,9 @@
 
 #include "device_common.h"
 #include "rptq_internal.h"
+#include "gemm_common.h"
 
 namespace rptq {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-struct GemmArgs {
-  const uint8_t* codes;      // packed activation codes, row-major
-  int64_t M;
-  int32_t row_bytes;         // K_p * bits / 8
-  const uint8_t* Wq;         // packed weights, fragment-major
-  int32_t N;
-  int32_t slices;            // K_p / 32
-  int32_t used_slices;       // slices up to the end of the last cluster
-  int32_t tiles_m, tiles_n;  // output tiles along M and N
-  const float* sW;
-  const int32_t* zW;
-  const float* colterm;
-  const float* rowterm;
-  void* y;
-  // verification mode
-  const int32_t* xsum;
-  const int32_t* wsum;
-  int32_t* yq;
-  int32_t first_round;       // workgroups resident at once (2 per compute unit); 0 = no start offset
-};
-
-struct GemmTab {
-  int32_t g;
-  int32_t slice_end[RPTQ_MAX_CLUSTERS];   // first slice after cluster i
-  float scale[RPTQ_MAX_CLUSTERS];         // (sX_i - sX_{i+1}) / 2^shift
-  int32_t zx[RPTQ_MAX_CLUSTERS];
-  int32_t n[RPTQ_MAX_CLUSTERS];           // channels in cluster i
-};
-
-constexpr int kStepSlices = 8;            // slices per K step (256 codes): one barrier per step
-constexpr int kSlicePad = 64;             // bytes added to a slice's LDS stride: 16 banks, so the four
-                                          // slices a 16-lane write group touches fall in distinct banks
-
-template <int BITS>
-struct ActFmt {
-  static constexpr int kGroupBytes = BITS * 4;             // bytes of 32 packed codes
-  static constexpr int kShift = (BITS == 8) ? 0 : (BITS == 4 ? 4 : 5);
-};
 
 // 16 bytes of 4-bit codes (32 codes) -> 32 int8 values (code << 4), natural order.
 __device__ __forceinline__ void unpack4(const uint4 p, uint4* lo, uint4* hi) {
@@ -103,14 +62,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  // The two workgroups of a compute unit would otherwise run in lockstep: both in the MFMA
-  // loop, then both in the output stage.  The second half of the first round starts a few
-  // microseconds late, so that one workgroup's stores and prologue run under the other's MFMAs;
-  // later workgroups take over a slot when it frees and inherit the offset.
-  if (static_cast<int>(blockIdx.x) < a.first_round && static_cast<int>(blockIdx.x) >= a.first_round / 2) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) __builtin_amdgcn_s_sleep(32);
-  }
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
   // contiguous band of output columns, all row tiles of one column tile back to back.
   const int tiles_m = a.tiles_m, tiles_n = a.tiles_n;
@@ -471,10 +422,6 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st)
   b.tiles_n = (a.N + BN - 1) / BN;
   b.tiles_m = static_cast<int32_t>((a.M + BM - 1) / BM);
   const dim3 grid(static_cast<unsigned>(b.tiles_n) * static_cast<unsigned>(b.tiles_m));
-  int dev = 0, cus = 0;
-  RPTQ_HIP(hipGetDevice(&dev));
-  RPTQ_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  b.first_round = (BM > 32 && grid.x >= 2u * static_cast<unsigned>(cus)) ? 2 * cus : 0;
   hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab);
   RPTQ_HIP(hipGetLastError());
   return RPTQ_OK;
