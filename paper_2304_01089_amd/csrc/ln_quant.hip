@@ -1,13 +1,15 @@
 // LayerNorm emitted in cluster order + per-cluster asymmetric quantization + bit packing
 // (Sec. 4.2 "fuse the reorder into layer norm"; Eq. 1; App. A.4 first equation).
 //
-// One workgroup owns whole rows and walks them in a grid-stride loop.  Each thread owns
-// the same output units (8 codes, or 16 for 3-bit) for every row, so everything that does
-// not depend on the row - source channel, gamma', beta', the cluster's quantizer constants
-// - is loaded once into registers.  Per row: coalesced 16-byte loads of the bf16 row,
-// exact fp64 row sums, one workgroup reduction (one barrier), then a gather of the row
-// through LDS in cluster order, the fp32 LayerNorm chain, round/offset/clamp, packing and
-// a coalesced store.  The next row's loads are issued before the gather of the current one.
+// One workgroup owns whole rows and walks them in a grid-stride loop.  Its last wave is the
+// statistics wave, all others are unit waves: a unit thread owns the same output units
+// (8 codes, or 16 for 3-bit) for every row, so everything that does not depend on the row -
+// source channel, gamma', beta', the cluster's quantizer constants - sits in registers.
+// The loop is pipelined over rows with one barrier per row.  Before the barrier the unit
+// threads put the next row into LDS (coalesced 16-byte loads, issued one iteration earlier)
+// and leave their exact fp64 partial sums there.  After it the statistics wave turns those
+// into the next row's mean and 1/std while the unit waves gather the current row through LDS
+// in cluster order, run the fp32 LayerNorm chain, round/offset/clamp, pack and store.
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
@@ -29,9 +31,8 @@ struct LnQuantArgs {
   float* rowterm;
   int32_t n_units;         // K_p / codes-per-unit
   int32_t row_bytes;       // K_p * bits / 8
+  int32_t ring;            // row buffers in LDS: 3, or 2 (one more barrier per row) when three do not fit
 };
-
-constexpr int kMaxChunk = 4;   // 16-byte chunks of the input row per thread
 
 template <int BITS>
 struct Unit {
@@ -46,7 +47,26 @@ __device__ __forceinline__ int pos3(int role, int e) {
   return 16 + role * 4 + (e - 12);
 }
 
-template <int BITS, int NUNIT, bool LN>
+// LDS: `ring` row buffers (bf16 row + a 16-byte slot for surplus lanes), then per parity the
+// partial sums of the unit threads ({S1, S2} and the de-quantized row sum), then per parity
+// {mean, 1/std}.
+struct LnLds {
+  int rowbuf_bytes;
+  int part12, part3, bcast;          // byte offsets
+};
+__host__ __device__ inline LnLds ln_lds_layout(int d, int ring, int tu) {
+  LnLds l;
+  l.rowbuf_bytes = d * 2 + 16;
+  l.part12 = ring * l.rowbuf_bytes;
+  l.part3 = l.part12 + 2 * tu * 16;
+  l.bcast = l.part3 + 2 * tu * 8;
+  return l;
+}
+
+// No load of this kernel sits under a lane-dependent branch: indices are clamped and what a
+// surplus lane computes is masked or never stored.  (A load under a divergent branch makes
+// the compiler wait for every load in flight at each such branch, which serializes them.)
+template <int BITS, int NUNIT, int NCH, bool LN>
 __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGeom geom, QuantTab qt) {
   constexpr int UC = Unit<BITS>::kCodes;
   constexpr int ND = UC / 4;                       // dwords of biased code bytes per unit
@@ -54,16 +74,62 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   constexpr int kQMin = -(1 << (BITS - 1));
 
   extern __shared__ __align__(16) unsigned char smem[];
-  const int rowbuf_bytes = a.d * 2;
-  double* red = reinterpret_cast<double*>(smem + 2 * rowbuf_bytes);      // [2][kMaxWaves][3]
-
   const int tid = threadIdx.x;
-  const int T = blockDim.x;
   const int lane = tid & (kWave - 1);
-  const int wid = tid >> 6;
-  const int nw = T >> 6;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
+  const int TU = static_cast<int>(blockDim.x) - kWave;          // unit threads; the last wave does the statistics
+  const int nwu = TU >> 6;
+  const bool stats_wave = wid == nwu;
+  const LnLds lds = ln_lds_layout(a.d, a.ring, TU);
+  double* part12 = reinterpret_cast<double*>(smem + lds.part12);   // [2][TU][2]
+  double* part3 = reinterpret_cast<double*>(smem + lds.part3);     // [2][TU]
+  float* bcast = reinterpret_cast<float*>(smem + lds.bcast);       // [2][2]
 
-  // ---- per-thread constants, loaded once ---------------------------------------
+  const int64_t row0 = blockIdx.x;
+  const int64_t stride = gridDim.x;
+  const int n_rows = static_cast<int>((a.M - row0 + stride - 1) / stride);   // >= 1: the grid has at most M workgroups
+
+  // Sum of the unit threads' partials in a fixed order: per lane over the waves, then over the lanes.
+  auto finalize_stats = [&](int pb) {
+    double s1 = 0.0, s2 = 0.0;
+    const double* p = part12 + (static_cast<size_t>(pb) * TU + lane) * 2;
+    for (int j = 0; j < nwu; ++j) {
+      const double2 v = *reinterpret_cast<const double2*>(p + j * 128);
+      s1 += v.x;
+      s2 += v.y;
+    }
+    const double t1 = wave_sum(s1), t2 = wave_sum(s2);
+    float mu, rstd;
+    row_stats(t1, t2, a.d, a.eps, &mu, &rstd);
+    if (lane == 0) {
+      bcast[pb * 2 + 0] = mu;
+      bcast[pb * 2 + 1] = rstd;
+    }
+  };
+  auto finalize_rowterm = [&](int pb, int64_t row) {
+    double s3 = 0.0;
+    const double* p = part3 + static_cast<size_t>(pb) * TU + lane;
+    for (int j = 0; j < nwu; ++j) s3 += p[j * 64];
+    const double t3 = wave_sum(s3);
+    if (lane == 0 && a.rowterm) a.rowterm[row] = static_cast<float>(t3);
+  };
+
+  if (stats_wave) {
+    // ---- statistics wave ---------------------------------------------------------------------
+    __syncthreads();                                           // row 0 staged
+    if (LN) finalize_stats(0);
+    for (int i = 0; i < n_rows; ++i) {
+      __syncthreads();                                         // row i+1 staged, row i-1 stored
+      if (LN) finalize_stats((i + 1) & 1);
+      if (i >= 1) finalize_rowterm((i - 1) & 1, row0 + (i - 1) * stride);
+      if (a.ring == 2) __syncthreads();
+    }
+    __syncthreads();
+    finalize_rowterm((n_rows - 1) & 1, row0 + (n_rows - 1) * stride);
+    return;
+  }
+
+  // ---- unit waves: per-thread constants, loaded once -----------------------------------------
   uint32_t src[NUNIT][UC / 2];       // LDS byte offsets of the source channels, two per register
   float gam[LN ? NUNIT : 1][LN ? UC : 1];
   float bet[LN ? NUNIT : 1][LN ? UC : 1];
@@ -71,14 +137,14 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   double sdq[NUNIT];                 // cluster scale, for the de-quantized row sum
   int32_t usum_fix[NUNIT];           // turns the sum of biased bytes into sum of (q - z) over real codes
   uint32_t keep[NUNIT][ND], fill[NUNIT][ND];
-  bool has_pad[NUNIT];
+  bool unit_ok[NUNIT];
   int64_t out_off[NUNIT];
 
 #pragma unroll
   for (int n = 0; n < NUNIT; ++n) {
-    const int u = tid + n * T;
-    const bool valid = u < a.n_units;
-    const int uu = valid ? u : 0;
+    const int u = tid + n * TU;
+    unit_ok[n] = u < a.n_units;
+    const int uu = unit_ok[n] ? u : 0;             // surplus lanes redo unit 0 and store nothing
     int gbase, role = 0;
     if (BITS == 3) {
       gbase = (uu >> 1) * kGroup;
@@ -88,30 +154,40 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
       gbase = uu * 8;
       out_off[n] = static_cast<int64_t>(uu) * BITS;
     }
-    if (!valid) out_off[n] = -1;
     int ci = 0;
     for (int i = 1; i < geom.g; ++i) ci += (gbase >= geom.pad_off[i]) ? 1 : 0;
     inv_s[n] = qt.inv_s[ci];
     zbf[n] = static_cast<float>(qt.zb[ci]);
     sdq[n] = static_cast<double>(qt.s[ci]);
+    // the unit's positions are runs of four consecutive padded positions: 16-byte loads
+    int32_t pc[UC];
+    float pg[UC], pb[UC];
+#pragma unroll
+    for (int v = 0; v < UC / 4; ++v) {
+      const int pos = (BITS == 3) ? gbase + pos3(role, v * 4) : gbase + v * 4;
+      const int4 c4 = *reinterpret_cast<const int4*>(a.perm_pad + pos);
+      pc[v * 4 + 0] = c4.x; pc[v * 4 + 1] = c4.y; pc[v * 4 + 2] = c4.z; pc[v * 4 + 3] = c4.w;
+      if (LN) {
+        const float4 g4 = *reinterpret_cast<const float4*>(a.gamma_pad + pos);
+        const float4 b4 = *reinterpret_cast<const float4*>(a.beta_pad + pos);
+        pg[v * 4 + 0] = g4.x; pg[v * 4 + 1] = g4.y; pg[v * 4 + 2] = g4.z; pg[v * 4 + 3] = g4.w;
+        pb[v * 4 + 0] = b4.x; pb[v * 4 + 1] = b4.y; pb[v * 4 + 2] = b4.z; pb[v * 4 + 3] = b4.w;
+      }
+    }
     int n_real = 0;
-    has_pad[n] = false;
 #pragma unroll
     for (int w = 0; w < ND; ++w) { keep[n][w] = 0xffffffffu; fill[n][w] = 0u; }
 #pragma unroll
     for (int e = 0; e < UC; ++e) {
-      const int pos = (BITS == 3) ? gbase + pos3(role, e) : gbase + e;
-      const int c = a.perm_pad[pos];
-      const bool real = c >= 0;
+      const bool real = pc[e] >= 0;
       n_real += real ? 1 : 0;
-      const uint32_t off = real ? static_cast<uint32_t>(c) * 2u : 0u;
+      const uint32_t off = real ? static_cast<uint32_t>(pc[e]) * 2u : 0u;
       if (e & 1) src[n][e / 2] |= off << 16; else src[n][e / 2] = off;
       if (LN) {
-        gam[n][e] = real ? a.gamma_pad[pos] : 0.0f;
-        bet[n][e] = real ? a.beta_pad[pos] : 0.0f;
+        gam[n][e] = real ? pg[e] : 0.0f;
+        bet[n][e] = real ? pb[e] : 0.0f;
       }
-      if (!real) {                               // pad position: force code 0 (biased byte = -qmin)
-        has_pad[n] = true;
+      if (!real) {                                 // pad position: force code 0 (biased byte = -qmin)
         keep[n][e / 4] &= ~(0xffu << (8 * (e & 3)));
         fill[n][e / 4] |= static_cast<uint32_t>(-kQMin) << (8 * (e & 3));
       }
@@ -119,73 +195,74 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     usum_fix[n] = UC * kQMin - n_real * qt.z[ci];
   }
 
-  // ---- row loop ------------------------------------------------------------------
-  uint4 nxt[kMaxChunk];
-  auto load_row = [&](int64_t row) {
+  // ---- this thread's 16-byte chunks of an input row ---------------------------------------
+  int ch_idx[NCH];                   // chunk index, clamped for surplus lanes
+  int ch_lds[NCH];                   // LDS byte offset inside a row buffer (surplus lanes: the spare slot)
+  bool ch_ok[NCH];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int idx = tid + c * TU;
+    ch_ok[c] = idx < a.chunks;
+    ch_idx[c] = ch_ok[c] ? idx : a.chunks - 1;
+    ch_lds[c] = ch_ok[c] ? idx * 16 : a.d * 2;
+  }
+  uint4 nxt[NCH];
+  auto load_row = [&](int k) {                       // k-th row of this workgroup; past the end: a valid row again
+    int64_t row = row0 + k * stride;
+    if (row >= a.M) row = a.M - 1;
     const uint4* p = a.x + row * a.chunks;
 #pragma unroll
-    for (int c = 0; c < kMaxChunk; ++c) {
-      const int idx = tid + c * T;
-      if (idx < a.chunks) nxt[c] = p[idx];
-    }
+    for (int c = 0; c < NCH; ++c) nxt[c] = p[ch_idx[c]];
   };
-
-  int64_t row = blockIdx.x;
-  if (row < a.M) load_row(row);
-  int parity = 0;
-  double rt_prev = 0.0;            // this thread's share of the previous row's de-quantized sum
-  int64_t prev_row = -1;
-
-  for (; row < a.M; row += gridDim.x, parity ^= 1) {
-    unsigned char* rowbuf = smem + parity * rowbuf_bytes;
+  // registers -> row buffer, exact fp64 sums of this thread's elements -> partials
+  auto stage_row = [&](unsigned char* rowbuf, int pb) {
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll
-    for (int c = 0; c < kMaxChunk; ++c) {
-      const int idx = tid + c * T;
-      if (idx < a.chunks) {
-        const uint4 v = nxt[c];
-        *reinterpret_cast<uint4*>(rowbuf + idx * 16) = v;
-        if (LN) {
-          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    for (int c = 0; c < NCH; ++c) {
+      uint4 v = nxt[c];
+      *reinterpret_cast<uint4*>(rowbuf + ch_lds[c]) = v;
+      if (LN) {
+        if (!ch_ok[c]) v = make_uint4(0u, 0u, 0u, 0u);       // surplus lane: contributes nothing
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const double lo = static_cast<double>(bf16_lo(w[k]));
-            const double hi = static_cast<double>(bf16_hi(w[k]));
-            s1 += lo;
-            s2 = fma(lo, lo, s2);
-            s1 += hi;
-            s2 = fma(hi, hi, s2);
-          }
+        for (int k = 0; k < 4; ++k) {
+          const double lo = static_cast<double>(bf16_lo(w[k]));
+          const double hi = static_cast<double>(bf16_hi(w[k]));
+          s1 += lo;
+          s2 = fma(lo, lo, s2);
+          s1 += hi;
+          s2 = fma(hi, hi, s2);
         }
       }
     }
-    const int64_t next_row = row + gridDim.x;
-    if (next_row < a.M) load_row(next_row);
+    if (LN) *reinterpret_cast<double2*>(part12 + (static_cast<size_t>(pb) * TU + tid) * 2) = make_double2(s1, s2);
+  };
 
-    // one reduction carries the row sums and the previous row's de-quantized sum
-    double* slot = red + parity * (kMaxWaves * 3);        // [3][kMaxWaves]
-    {
-      const double r1 = wave_sum(s1), r2 = wave_sum(s2), r3 = wave_sum(rt_prev);
-      if (lane == 0) {
-        slot[0 * kMaxWaves + wid] = r1;
-        slot[1 * kMaxWaves + wid] = r2;
-        slot[2 * kMaxWaves + wid] = r3;
-      }
-    }
-    __syncthreads();
-    const double t1 = partials_sum(slot + 0 * kMaxWaves, nw, lane);
-    const double t2 = partials_sum(slot + 1 * kMaxWaves, nw, lane);
-    const double t3 = partials_sum(slot + 2 * kMaxWaves, nw, lane);
-    if (tid == 0 && prev_row >= 0 && a.rowterm) a.rowterm[prev_row] = static_cast<float>(t3);
+  // ---- pipelined row loop --------------------------------------------------------------------
+  int b_cur = 0, b_next = lds.rowbuf_bytes, b_spare = (a.ring == 3) ? 2 * lds.rowbuf_bytes : 0;
+  load_row(0);
+  stage_row(smem + b_cur, 0);
+  load_row(1);
+  __syncthreads();                                             // row 0 staged
+
+  for (int i = 0; i < n_rows; ++i) {
+    stage_row(smem + b_next, (i + 1) & 1);
+    load_row(i + 2);
+    __syncthreads();                                           // row i+1 staged; {mean, 1/std} of row i published
+    const unsigned char* rowbuf = smem + b_cur;
     float mu = 0.0f, rstd = 1.0f;
-    if (LN) row_stats(t1, t2, a.d, a.eps, &mu, &rstd);
+    if (LN) {
+      const float2 ms = *reinterpret_cast<const float2*>(bcast + (i & 1) * 2);
+      mu = ms.x;
+      rstd = ms.y;
+    }
+    const int64_t row = row0 + i * stride;
 
     // ---- gather in cluster order, normalize, quantize, pack ------------------------
     double rt = 0.0;
     uint8_t* out_row = a.codes + row * a.row_bytes;
 #pragma unroll
     for (int n = 0; n < NUNIT; ++n) {
-      if (out_off[n] < 0) continue;
       uint32_t D[ND];
 #pragma unroll
       for (int w = 0; w < ND; ++w) D[w] = 0u;
@@ -201,22 +278,22 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
         if (BITS < 8) b = fminf(b, kUMax);              // upper clamp; the conversion saturates at 0 and 255
         D[e / 4] = __builtin_amdgcn_cvt_pk_u8_f32(b, e & 3, D[e / 4]);
       }
-      if (has_pad[n]) {
 #pragma unroll
-        for (int w = 0; w < ND; ++w) D[w] = (D[w] & keep[n][w]) | fill[n][w];
-      }
+      for (int w = 0; w < ND; ++w) D[w] = (D[w] & keep[n][w]) | fill[n][w];      // pad positions: code 0
       uint32_t usum = 0;
 #pragma unroll
       for (int w = 0; w < ND; ++w) usum = __builtin_amdgcn_sad_u8(D[w], 0u, usum);
-      rt += sdq[n] * static_cast<double>(static_cast<int32_t>(usum) + usum_fix[n]);
+      const double part = sdq[n] * static_cast<double>(static_cast<int32_t>(usum) + usum_fix[n]);
+      rt += unit_ok[n] ? part : 0.0;
 
       if (BITS == 8) {
         uint2 o;
         o.x = D[0] ^ 0x80808080u;
         o.y = D[1] ^ 0x80808080u;
-        *reinterpret_cast<uint2*>(out_row + out_off[n]) = o;
+        if (unit_ok[n]) *reinterpret_cast<uint2*>(out_row + out_off[n]) = o;
       } else if (BITS == 4) {
-        *reinterpret_cast<uint32_t*>(out_row + out_off[n]) = ((D[0] << 4) | D[1]) ^ 0x88888888u;
+        const uint32_t o = ((D[0] << 4) | D[1]) ^ 0x88888888u;
+        if (unit_ok[n]) *reinterpret_cast<uint32_t*>(out_row + out_off[n]) = o;
       } else {
         // role 0 -> x0 and its half of x2; role 1 -> x1 and its half of x2 (partner = lane ^ 1)
         const uint32_t w1 = ((D[0] << 5) | (D[1] << 2) | ((D[2] >> 1) & 0x03030303u)) ^ 0x80808080u ^ 0x10101010u ^ 0x02020202u;
@@ -224,28 +301,22 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
         const uint32_t mine = role ? (((D[3] << 2) ^ 0x10101010u) | ((D[2] & 0x01010101u) << 1))
                                    : (((D[3] << 5) ^ 0x80808080u) | (D[2] & 0x01010101u));
         const uint32_t other = __shfl_xor(mine, 1, kWave);
-        if (role == 0) {
-          *reinterpret_cast<uint32_t*>(out_row + out_off[n]) = w1;
-        } else {
+        if (unit_ok[n]) {
           uint32_t* p = reinterpret_cast<uint32_t*>(out_row + out_off[n]);
           p[0] = w1;
-          p[1] = mine | other;
+          if (role) p[1] = mine | other;
         }
       }
     }
-    rt_prev = rt;
-    prev_row = row;
+    part3[static_cast<size_t>(i & 1) * TU + tid] = rt;
+    if (a.ring == 2) {
+      __syncthreads();                                         // two row buffers only: all gathers done before the next staging
+      const int t = b_cur; b_cur = b_next; b_next = t;
+    } else {
+      const int t = b_cur; b_cur = b_next; b_next = b_spare; b_spare = t;
+    }
   }
-
-  // flush the last row's de-quantized sum
-  if (prev_row >= 0 && a.rowterm) {
-    double* slot = red + parity * (kMaxWaves * 3);
-    const double r3 = wave_sum(rt_prev);
-    if (lane == 0) slot[2 * kMaxWaves + wid] = r3;
-    __syncthreads();
-    const double t3 = partials_sum(slot + 2 * kMaxWaves, nw, lane);
-    if (tid == 0) a.rowterm[prev_row] = static_cast<float>(t3);
-  }
+  __syncthreads();                                             // last row's partial sums are in LDS
 }
 
 // Per-cluster sums of the packed codes (verification output of rptq_ln_quant).
@@ -300,32 +371,53 @@ __global__ void unpack_codes_kernel(const uint8_t* codes, int64_t rows, int32_t 
 }
 
 // ---------------------------------------------------------------------------------------
-template <int BITS, int NUNIT>
-static int32_t launch_one(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, bool ln, int threads,
-                          int grid, size_t shmem, hipStream_t st) {
-  auto k_ln = ln_quant_kernel<BITS, NUNIT, true>;
-  auto k_plain = ln_quant_kernel<BITS, NUNIT, false>;
+constexpr int kMaxChunk = 4;   // 16-byte chunks of the input row per unit thread
+constexpr int kMaxUnitThreads = 1024 - kWave;
+
+template <int BITS, int NUNIT, int NCH, bool LN>
+static int32_t launch_kernel(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, int threads,
+                             int64_t want_grid, int lds_per_cu, size_t shmem, hipStream_t st) {
+  auto kern = ln_quant_kernel<BITS, NUNIT, NCH, LN>;
   if (shmem > 64 * 1024) {
-    RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(ln ? k_ln : k_plain),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
+    RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 static_cast<int>(shmem)));
   }
-  if (ln) {
-    hipLaunchKernelGGL(k_ln, dim3(grid), dim3(threads), shmem, st, a, geom, qt);
-  } else {
-    hipLaunchKernelGGL(k_plain, dim3(grid), dim3(threads), shmem, st, a, geom, qt);
-  }
+  // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round
+  int per_cu = 0;
+  RPTQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, shmem));
+  if (per_cu < 1) per_cu = 1;
+  (void)lds_per_cu;
+  const int64_t grid = std::min<int64_t>(a.M, want_grid * per_cu);
+  hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(threads), shmem, st, a, geom, qt);
   RPTQ_HIP(hipGetLastError());
   return RPTQ_OK;
 }
 
+template <int BITS, int NUNIT, bool LN>
+static int32_t launch_chunks(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, int nch, int threads,
+                             int64_t cus, int lds_per_cu, size_t shmem, hipStream_t st) {
+  if (nch <= 1) return launch_kernel<BITS, NUNIT, 1, LN>(a, geom, qt, threads, cus, lds_per_cu, shmem, st);
+  if (nch == 2) return launch_kernel<BITS, NUNIT, 2, LN>(a, geom, qt, threads, cus, lds_per_cu, shmem, st);
+  return launch_kernel<BITS, NUNIT, kMaxChunk, LN>(a, geom, qt, threads, cus, lds_per_cu, shmem, st);
+}
+
+// With LayerNorm a thread keeps gamma' and beta' of its units in registers: at most two units
+// (one of 16 codes at 3 bits); without, up to four (two).
 template <int BITS>
 static int32_t launch_bits(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, bool ln, int nunit,
-                           int threads, int grid, size_t shmem, hipStream_t st) {
-  switch (nunit) {
-    case 1: return launch_one<BITS, 1>(a, geom, qt, ln, threads, grid, shmem, st);
-    case 2: return launch_one<BITS, 2>(a, geom, qt, ln, threads, grid, shmem, st);
-    case 3: return launch_one<BITS, 3>(a, geom, qt, ln, threads, grid, shmem, st);
-    default: return launch_one<BITS, 4>(a, geom, qt, ln, threads, grid, shmem, st);
+                           int nch, int threads, int64_t cus, int lds_per_cu, size_t shmem, hipStream_t st) {
+  if constexpr (BITS == 3) {
+    if (ln) return launch_chunks<3, 1, true>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+    if (nunit == 1) return launch_chunks<3, 1, false>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+    return launch_chunks<3, 2, false>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+  } else {
+    if (ln) {
+      if (nunit == 1) return launch_chunks<BITS, 1, true>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+      return launch_chunks<BITS, 2, true>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+    }
+    if (nunit == 1) return launch_chunks<BITS, 1, false>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+    if (nunit == 2) return launch_chunks<BITS, 2, false>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
+    return launch_chunks<BITS, 4, false>(a, geom, qt, nch, threads, cus, lds_per_cu, shmem, st);
   }
 }
 
@@ -350,19 +442,20 @@ int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_
   a.n_units = geom.k_padded / uc;
   a.row_bytes = geom.k_padded * bits / 8;
 
-  // Threads: enough for the input chunks (<= kMaxChunk per thread) and the units (<= 4 per
-  // thread), a multiple of the wave size, as few idle lanes in the unit phase as possible.
+  // Unit threads: enough for the units (<= max_nunit per thread) and the input chunks
+  // (<= kMaxChunk per thread), a multiple of the wave size, as few idle lanes as possible.
   const bool ln = gamma_pad != nullptr;
-  // register budget at 1024 threads: per-unit constants of more units than this would spill
+  // register budget: per-unit constants of more units than this would spill
   const int max_nunit = ln ? (bits == 3 ? 1 : 2) : (bits == 3 ? 2 : 4);
   int best_t = 0, best_n = 0;
   double best_waste = 1e30;
   for (int nunit = 1; nunit <= max_nunit; ++nunit) {
+    if (nunit == 3) continue;                      // instantiated: 1, 2, 4
     int t = (a.n_units + nunit - 1) / nunit;
     t = (t + kWave - 1) / kWave * kWave;
     const int t_chunks = ((a.chunks + kMaxChunk - 1) / kMaxChunk + kWave - 1) / kWave * kWave;
     if (t < t_chunks) t = t_chunks;
-    if (t > 1024) continue;
+    if (t > kMaxUnitThreads) continue;
     if (t < 256 && nunit > 1) continue;
     const double waste = static_cast<double>(t) * nunit / a.n_units;
     if (waste < best_waste - 1e-9) {
@@ -372,21 +465,27 @@ int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_
     }
   }
   if (best_t == 0) return RPTQ_ERR_SHAPE;
+  const int nch = (a.chunks + best_t - 1) / best_t;          // 1, 2 or 3..4 (run as 4)
 
   int dev = 0, cus = 256;
   RPTQ_HIP(hipGetDevice(&dev));
   RPTQ_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  const size_t shmem = static_cast<size_t>(d) * 4 + 2 * kMaxWaves * 3 * sizeof(double);
-  if (shmem > 160 * 1024) return RPTQ_ERR_SHAPE;
-  int per_cu = static_cast<int>(std::min<size_t>(1024 / best_t, (160 * 1024) / shmem));
-  if (per_cu < 1) per_cu = 1;
-  const int64_t grid64 = std::min<int64_t>(M, static_cast<int64_t>(cus) * per_cu);
-  const int grid = static_cast<int>(grid64);
+  const int lds_cu = 160 * 1024;
+  a.ring = 3;
+  LnLds lay = ln_lds_layout(d, 3, best_t);
+  size_t shmem = static_cast<size_t>(lay.bcast) + 16;
+  if (shmem > static_cast<size_t>(lds_cu)) {
+    a.ring = 2;
+    lay = ln_lds_layout(d, 2, best_t);
+    shmem = static_cast<size_t>(lay.bcast) + 16;
+  }
+  if (shmem > static_cast<size_t>(lds_cu)) return RPTQ_ERR_SHAPE;
+  const int threads = best_t + kWave;
 
   int32_t stt;
-  if (bits == 3) stt = launch_bits<3>(a, geom, qt, ln, best_n, best_t, grid, shmem, st);
-  else if (bits == 4) stt = launch_bits<4>(a, geom, qt, ln, best_n, best_t, grid, shmem, st);
-  else stt = launch_bits<8>(a, geom, qt, ln, best_n, best_t, grid, shmem, st);
+  if (bits == 3) stt = launch_bits<3>(a, geom, qt, ln, best_n, nch, threads, cus, lds_cu, shmem, st);
+  else if (bits == 4) stt = launch_bits<4>(a, geom, qt, ln, best_n, nch, threads, cus, lds_cu, shmem, st);
+  else stt = launch_bits<8>(a, geom, qt, ln, best_n, nch, threads, cus, lds_cu, shmem, st);
   if (stt) return stt;
 
   if (xsum) {
