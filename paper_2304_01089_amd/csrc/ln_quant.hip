@@ -130,7 +130,7 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   }
 
   // ---- unit waves: per-thread constants, loaded once -----------------------------------------
-  uint32_t src[NUNIT][UC / 2];       // LDS byte offsets of the source channels, two per register
+  uint32_t src[NUNIT][UC];           // LDS byte offsets of the source channels inside a row buffer
   float gam[LN ? NUNIT : 1][LN ? UC : 1];
   float bet[LN ? NUNIT : 1][LN ? UC : 1];
   float inv_s[NUNIT], zbf[NUNIT];
@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
       const bool real = pc[e] >= 0;
       n_real += real ? 1 : 0;
       const uint32_t off = real ? static_cast<uint32_t>(pc[e]) * 2u : 0u;
-      if (e & 1) src[n][e / 2] |= off << 16; else src[n][e / 2] = off;
+      src[n][e] = off;
       if (LN) {
         gam[n][e] = real ? pg[e] : 0.0f;
         bet[n][e] = real ? pb[e] : 0.0f;
@@ -238,6 +238,8 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     if (LN) *reinterpret_cast<double2*>(part12 + (static_cast<size_t>(pb) * TU + tid) * 2) = make_double2(s1, s2);
   };
 
+  const float relu_floor = a.relu ? 0.0f : -__builtin_huge_valf();
+
   // ---- pipelined row loop --------------------------------------------------------------------
   int b_cur = 0, b_next = lds.rowbuf_bytes, b_spare = (a.ring == 3) ? 2 * lds.rowbuf_bytes : 0;
   load_row(0);
@@ -268,11 +270,10 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
       for (int w = 0; w < ND; ++w) D[w] = 0u;
 #pragma unroll
       for (int e = 0; e < UC; ++e) {
-        const uint32_t off = (e & 1) ? (src[n][e / 2] >> 16) : (src[n][e / 2] & 0xffffu);
-        const uint32_t h = *reinterpret_cast<const uint16_t*>(rowbuf + off);
+        const uint32_t h = *reinterpret_cast<const uint16_t*>(rowbuf + src[n][e]);
         float y = __uint_as_float(h << 16);
         if (LN) y = ln_chain(y, mu, rstd, gam[n][e], bet[n][e]);
-        if (a.relu) y = fmaxf(y, 0.0f);
+        y = fmaxf(y, relu_floor);                        // ReLU sites: 0; otherwise -inf (no effect)
         const float r = __fmul_rn(y, inv_s[n]);
         float b = __fadd_rn(rintf(r), zbf[n]);          // round, then add the zero point (biased by -qmin)
         if (BITS < 8) b = fminf(b, kUMax);              // upper clamp; the conversion saturates at 0 and 255
