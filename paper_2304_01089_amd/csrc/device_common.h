@@ -53,15 +53,22 @@ __device__ __forceinline__ double partials_sum(const double* p, int nw, int lane
 }
 
 // Row statistics of LayerNorm from exact fp64 sums of the bf16 inputs:
-// mean = S1/d, var = (S2 - S1*S1/d)/d (biased), rstd = 1/sqrt(var+eps); both rounded once to fp32.
+// mean = S1/d, var = (S2 - S1*mean)/d (biased), rstd = 1/sqrt(var+eps); both rounded once to fp32.
+// The fp64 values are formed with a reciprocal of d and a Newton-refined reciprocal square root
+// (a short dependent chain); they differ from the divide/sqrt forms by a few units in the last
+// fp64 place, far inside the margin at which a row counts as having a fragile fp32 rounding.
 __device__ __forceinline__ void row_stats(double s1, double s2, int d, float eps, float* mu32, float* rstd32) {
-  const double dd = static_cast<double>(d);
-  const double mu = s1 / dd;
-  double var = (s2 - s1 * mu) / dd;
+  const double inv_d = 1.0 / static_cast<double>(d);            // (uniform; hoisted out of row loops)
+  const double mu = s1 * inv_d;
+  double var = fma(-s1, mu, s2) * inv_d;
   var = var < 0.0 ? 0.0 : var;
-  const double rstd = 1.0 / sqrt(var + static_cast<double>(eps));
+  const double x = var + static_cast<double>(eps);
+  double y = __builtin_amdgcn_rsq(x);                           // about 2^-26 relative
+  y = y * fma(-0.5 * x * y, y, 1.5);
+  y = y * fma(-0.5 * x * y, y, 1.5);
+  y = y * fma(-0.5 * x * y, y, 1.5);
   *mu32 = static_cast<float>(mu);
-  *rstd32 = static_cast<float>(rstd);
+  *rstd32 = static_cast<float>(y);
 }
 
 // The four separately rounded fp32 operations of the LayerNorm chain (no contraction).

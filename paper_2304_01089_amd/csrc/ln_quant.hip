@@ -93,10 +93,16 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   auto finalize_stats = [&](int pb) {
     double s1 = 0.0, s2 = 0.0;
     const double* p = part12 + (static_cast<size_t>(pb) * TU + lane) * 2;
-    for (int j = 0; j < nwu; ++j) {
-      const double2 v = *reinterpret_cast<const double2*>(p + j * 128);
-      s1 += v.x;
-      s2 += v.y;
+    for (int j = 0; j < nwu; j += 4) {                            // four reads in flight; surplus slots re-read wave 0
+      double2 v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const double2*>(p + ((j + k) < nwu ? (j + k) : 0) * 128);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const bool in = (j + k) < nwu;
+        s1 += in ? v[k].x : 0.0;
+        s2 += in ? v[k].y : 0.0;
+      }
     }
     const double t1 = wave_sum(s1), t2 = wave_sum(s2);
     float mu, rstd;
@@ -109,13 +115,22 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   auto finalize_rowterm = [&](int pb, int64_t row) {
     double s3 = 0.0;
     const double* p = part3 + static_cast<size_t>(pb) * TU + lane;
-    for (int j = 0; j < nwu; ++j) s3 += p[j * 64];
+    for (int j = 0; j < nwu; j += 4) {
+      double v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = p[((j + k) < nwu ? (j + k) : 0) * 64];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s3 += (j + k) < nwu ? v[k] : 0.0;
+    }
     const double t3 = wave_sum(s3);
     if (lane == 0 && a.rowterm) a.rowterm[row] = static_cast<float>(t3);
   };
 
   if (stats_wave) {
     // ---- statistics wave ---------------------------------------------------------------------
+    // Its dependent chain per row must stay shorter than the unit waves' work on a row: it
+    // issues ahead of the unit waves that share its SIMD.
+    __builtin_amdgcn_s_setprio(3);
     __syncthreads();                                           // row 0 staged
     if (LN) finalize_stats(0);
     for (int i = 0; i < n_rows; ++i) {
