@@ -31,8 +31,10 @@ EPS = 1e-5
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--ramp-s", type=float, default=1.0,
+                    help="seconds of untimed steps before the warmup (the GPU clocks need about a second of load to settle)")
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: OPT-1.3b layer)")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/weight copies cycled through the steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -119,6 +121,11 @@ def main():
                     events.append(("gemm:%s" % lin["name"], e0, e1))
 
     # ---- whole-step throughput ------------------------------------------------------------------
+    t_ramp = time.time()
+    while time.time() - t_ramp < args.ramp_s:   # untimed: brings the clocks to their loaded state
+        for i in range(50):
+            step(i)
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

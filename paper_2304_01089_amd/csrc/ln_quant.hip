@@ -398,10 +398,18 @@ static int32_t launch_kernel(const LnQuantArgs& a, const ClusterGeom& geom, cons
     RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  static_cast<int>(shmem)));
   }
-  // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round
-  int per_cu = 0;
-  RPTQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, shmem));
-  if (per_cu < 1) per_cu = 1;
+  // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round.
+  // (the last answer is kept: a serving loop asks for the same launch shape again and again)
+  static int cached_threads = -1, cached_per_cu = 0;
+  static size_t cached_shmem = 0;
+  int per_cu = cached_per_cu;
+  if (cached_threads != threads || cached_shmem != shmem) {
+    RPTQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, shmem));
+    if (per_cu < 1) per_cu = 1;
+    cached_per_cu = per_cu;
+    cached_shmem = shmem;
+    cached_threads = threads;
+  }
   (void)lds_per_cu;
   const int64_t grid = std::min<int64_t>(a.M, want_grid * per_cu);
   hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(threads), shmem, st, a, geom, qt);
@@ -483,9 +491,12 @@ int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_
   if (best_t == 0) return RPTQ_ERR_SHAPE;
   const int nch = (a.chunks + best_t - 1) / best_t;          // 1, 2 or 3..4 (run as 4)
 
-  int dev = 0, cus = 256;
-  RPTQ_HIP(hipGetDevice(&dev));
-  RPTQ_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  static int cus = 0;                              // compute units of the device (one device type per process)
+  if (cus == 0) {
+    int dev = 0;
+    RPTQ_HIP(hipGetDevice(&dev));
+    RPTQ_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  }
   const int lds_cu = 160 * 1024;
   a.ring = 3;
   LnLds lay = ln_lds_layout(d, 3, best_t);

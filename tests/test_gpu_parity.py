@@ -70,6 +70,10 @@ CASES = {
     "mid_a3": dict(seed=16, d=1024, M=300, g=16, bits=3, N=520, n_cal=4, cal_rows=64),
     "mid_a4": dict(seed=17, d=2048, M=257, g=16, bits=4, N=384, n_cal=4, cal_rows=64),
     "decode_a3": dict(seed=18, d=1536, M=16, g=32, bits=3, N=1024, n_cal=4, cal_rows=64),
+    # a row too wide for three LDS row buffers (two buffers, one more barrier per row), four
+    # input chunks and four units per thread
+    "wide_relu": dict(seed=19, d=24576, M=9, g=8, bits=4, N=32, n_cal=2, cal_rows=16, ln=False, relu=True),
+    "one_row": dict(seed=20, d=512, M=1, g=4, bits=3, N=64),
 }
 _cache = {}
 
