@@ -73,7 +73,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   // ---- global -> register staging ------------------------------------------------------
   uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run ahead of use
-  uint4 wreg[2][WN][kStepSlices / 2];                     // this lane's weight bytes: [set][block][slice pair]
+  uint4 wreg[WN][kStepSlices / 2];                        // this lane's weight bytes of one K step: [block][slice pair]
   const uint8_t* a_ptr[A_PER];
   const uint8_t* w_ptr[WN];
   int a_lds[A_PER];
@@ -103,17 +103,17 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     for (int i = 0; i < A_PER; ++i) load_a_unit(step, q, i);
   };
   // one slice pair (32 bytes per lane) of weight block j
-  auto load_w_pair = [&](int step, int q, int j, int pi) {
-    wreg[q][j][pi] = *reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + (pi >> 1)) * 2048 + (pi & 1) * 16);
+  auto load_w_pair = [&](int step, int j, int pi) {
+    wreg[j][pi] = *reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + (pi >> 1)) * 2048 + (pi & 1) * 16);
   };
-  auto load_w = [&](int step, int q) {
+  auto load_w = [&](int step) {
 #pragma unroll
     for (int j = 0; j < WN; ++j) {
 #pragma unroll
       for (int b = 0; b < kStepSlices / 4; ++b) {           // one 2 KiB weight block per four slices
         const uint4* p = reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + b) * 2048);
-        wreg[q][j][2 * b] = p[0];
-        wreg[q][j][2 * b + 1] = p[1];
+        wreg[j][2 * b] = p[0];
+        wreg[j][2 * b + 1] = p[1];
       }
     }
   };
@@ -169,17 +169,16 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   // Pipeline.  Activations: LDS holds two stages; while stage p feeds the MFMAs of K step
   // `step`, the registers loaded earlier are unpacked into stage p^1 between those MFMAs.
-  // Weights: register set p feeds step `step`.  Every staging register is refilled right after
-  // its last use - activations with the data of step+3, weights with step+2 - so each load has
-  // two full steps to arrive.
+  // Weights: one register set holds a step; a slice pair is refilled with the next step's bytes
+  // right after its last use, seven slices before it is needed again.  Activation staging
+  // registers are refilled after use with the data of step+3.
   // (step indices are clamped to the last step instead of guarding the loads: a load that is
   // always issued lets the compiler count outstanding loads exactly, and the surplus data of
   // the tail is never used)
   const int last = steps - 1;
   load_a(0, 0);
-  load_w(0, 0);
+  load_w(0);
   load_a(min(1, last), 1);
-  load_w(min(1, last), 1);
 #pragma unroll
   for (int u = 0; u < A_PER; ++u) {
     store_a_half(0, 0, u, 0);
@@ -192,8 +191,8 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   load_a(min(2, last), 0);
 
   v4i fb[2][WN];                                            // weight fragments (code << 4), one slice ahead
-  auto unpack_w = [&](int q, int set, int s, int j) {       // fb[q][j] <- slice s of weight set `set`
-    const uint4 w = wreg[set][j][s >> 1];
+  auto unpack_w = [&](int q, int s, int j) {                // fb[q][j] <- slice s of the staged weights
+    const uint4 w = wreg[j][s >> 1];
     const uint32_t x = (s & 1) ? w.z : w.x, y = (s & 1) ? w.w : w.y;
     fb[q][j][0] = static_cast<int>(x & 0xf0f0f0f0u);
     fb[q][j][1] = static_cast<int>((x << 4) & 0xf0f0f0f0u);
@@ -201,7 +200,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     fb[q][j][3] = static_cast<int>((y << 4) & 0xf0f0f0f0u);
   };
 #pragma unroll
-  for (int j = 0; j < WN; ++j) unpack_w(0, 0, 0, j);
+  for (int j = 0; j < WN; ++j) unpack_w(0, 0, j);
 
   auto k_step = [&](int step, auto parity) {
     constexpr int buf = decltype(parity)::value;            // LDS stage / weight set read by this step
@@ -212,7 +211,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       for (int i = 0; i < WM; ++i) fa[q][i] = *reinterpret_cast<const v4i*>(cA + s * A_SLICE + a_frag + i * 32 * 16);
     };
     load_frags(0, 0);
-    const int w_step = min(step + 2, last), a_step = min(step + 3, last);
+    const int w_step = min(step + 1, last), a_step = min(step + 3, last);
     auto do_slice = [&](auto s_tag) {
       constexpr int s = decltype(s_tag)::value;
       // One basic block per slice: the MFMAs of this slice with, between them, everything else
@@ -232,8 +231,8 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
         auto piece = [&](int k) {
           if (k < WN) {
             // (on the last step the "next" data is stale and its results are never used)
-            if (s + 1 < kStepSlices) unpack_w((s + 1) & 1, buf, s + 1, k);
-            else unpack_w(0, buf ^ 1, 0, k);
+            if (s + 1 < kStepSlices) unpack_w((s + 1) & 1, s + 1, k);
+            else unpack_w(0, 0, k);              // pair 0 already holds the next step
           } else {
             const int h = k - WN;
             store_a_half(buf ^ 1, buf ^ 1, u_lo + (h >> 1), h & 1);
@@ -247,9 +246,9 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
           for (int k = m; k < NP; k += NM) piece(k);
         }
         // refill the staging registers this slice has finished with
-        if (s & 1) {
+        if ((s & 1) == 0) {                                // pair s/2: its second slice was expanded just above
 #pragma unroll
-          for (int j = 0; j < WN; ++j) load_w_pair(w_step, buf, j, s >> 1);
+          for (int j = 0; j < WN; ++j) load_w_pair(w_step, j, s >> 1);
         }
 #pragma unroll
         for (int u = u_lo; u < u_hi; ++u) load_a_unit(a_step, buf ^ 1, u);
