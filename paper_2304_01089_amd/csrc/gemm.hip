@@ -74,29 +74,47 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   // ---- global -> register staging ------------------------------------------------------
   uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run ahead of use
   uint4 wreg[WN][kStepSlices / 2];                        // this lane's weight bytes of one K step: [block][slice pair]
-  const uint8_t* a_ptr[A_PER];
-  const uint8_t* w_ptr[WN];
+  // Operands are read with buffer loads (a resource descriptor per workgroup, a 32-bit offset
+  // per lane): next to a busy matrix pipe this path sustains about twice the bytes per clock of
+  // loads that carry a 64-bit address per lane.
+  typedef unsigned u4v __attribute__((ext_vector_type(4)));
+  typedef unsigned u3v __attribute__((ext_vector_type(3)));
+  constexpr int kRsrcFlags = 0x00020000;                   // raw buffer, 32-bit data format
+  int a_off[A_PER], w_off[WN];                             // byte offsets inside the workgroup's operand windows
   int a_lds[A_PER];
+  const int64_t rows_here = (a.M - m0) < BM ? (a.M - m0) : BM;             // rows of this tile that exist (>= 1)
 #pragma unroll
   for (int i = 0; i < A_PER; ++i) {
     // surplus threads repeat a valid unit (same bytes to the same LDS address): no divergent
     // branches around the loads, so all of a step's loads are in flight together
     const int unit = (tid + i * 256) % A_UNITS;
     const int row = unit / kStepSlices, s = unit % kStepSlices;
-    int64_t grow = m0 + row;
-    if (grow >= a.M) grow = a.M - 1;                       // clamp: loads stay in bounds, rows never stored
-    a_ptr[i] = a.codes + grow * a.row_bytes + s * GB;
+    const int lrow = row < rows_here ? row : static_cast<int>(rows_here) - 1;   // clamp: rows past M are never stored
+    a_off[i] = lrow * a.row_bytes + s * GB;
     a_lds[i] = s * A_SLICE + row * 16;
   }
   const int wblocks = a.slices / (kWBlockCols / kGroup);   // packed weight blocks per 32-row band
 #pragma unroll
-  for (int j = 0; j < WN; ++j)
-    w_ptr[j] = a.Wq + (static_cast<size_t>(n0 / 32 + wn * WN + j) * wblocks * 64 + lane) * 32;
+  for (int j = 0; j < WN; ++j) w_off[j] = ((wn * WN + j) * wblocks * 64 + lane) * 32;
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(a.codes) + m0 * a.row_bytes, 0, static_cast<int>(rows_here) * a.row_bytes, kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(a.Wq) + static_cast<size_t>(n0 / 32) * wblocks * 2048, 0, (BN / 32) * wblocks * 2048, kRsrcFlags);
 
   auto load_a_unit = [&](int step, int q, int i) {
-    const uint32_t* p = reinterpret_cast<const uint32_t*>(a_ptr[i] + static_cast<size_t>(step) * kStepSlices * GB);
+    const int soff = step * (kStepSlices * GB);
+    if (A_REGS == 3) {
+      const u3v r = __builtin_amdgcn_raw_buffer_load_b96(a_rsrc, a_off[i], soff, 0);
 #pragma unroll
-    for (int k = 0; k < A_REGS; ++k) ra[q][i][k] = p[k];
+      for (int k = 0; k < 3; ++k) ra[q][i][k % A_REGS] = r[k];
+    } else {
+#pragma unroll
+      for (int h = 0; h < A_REGS / 4; ++h) {
+        const u4v r = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, a_off[i] + h * 16, soff, 0);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ra[q][i][(h * 4 + k) % A_REGS] = r[k];
+      }
+    }
   };
   auto load_a = [&](int step, int q) {
 #pragma unroll
@@ -104,18 +122,15 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   };
   // one slice pair (32 bytes per lane) of weight block j
   auto load_w_pair = [&](int step, int j, int pi) {
-    wreg[j][pi] = *reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + (pi >> 1)) * 2048 + (pi & 1) * 16);
+    const u4v r = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_off[j] + (pi & 1) * 16,
+                                                        (step * (kStepSlices / 4) + (pi >> 1)) * 2048, 0);
+    wreg[j][pi] = make_uint4(r[0], r[1], r[2], r[3]);
   };
   auto load_w = [&](int step) {
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
+    for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int b = 0; b < kStepSlices / 4; ++b) {           // one 2 KiB weight block per four slices
-        const uint4* p = reinterpret_cast<const uint4*>(w_ptr[j] + (static_cast<size_t>(step) * (kStepSlices / 4) + b) * 2048);
-        wreg[j][2 * b] = p[0];
-        wreg[j][2 * b + 1] = p[1];
-      }
-    }
+      for (int pi = 0; pi < kStepSlices / 2; ++pi) load_w_pair(step, j, pi);
   };
 
   // unpack one half (16 codes) of a staged unit to int8 and write it to LDS stage `buf`
@@ -339,17 +354,29 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     const int cc = tid % CPR, rr = tid / CPR;
     const int n = n0 + cc * CW;
     float sw[CW], ct[CW], zw[CW], rt[NPASS];
+    {
+      // (buffer loads: 16 bytes at a time, reads past the end of a vector return 0 and belong to
+      // outputs that are never stored)
+      const __amdgpu_buffer_rsrc_t sw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.sW), 0, a.N * 4, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t ct_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.colterm), 0, a.N * 4, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t zw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.zW), 0, a.N * 4, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t rt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<float*>(a.rowterm) + m0, 0, static_cast<int>(rows_here) * 4, kRsrcFlags);
 #pragma unroll
-    for (int e = 0; e < CW; ++e) {
-      const int nc = (n + e) < a.N ? (n + e) : a.N - 1;     // clamped: always in bounds
-      sw[e] = a.sW[nc];
-      ct[e] = a.colterm[nc];
-      zw[e] = static_cast<float>(a.zW[nc]);
-    }
+      for (int e4 = 0; e4 < CW / 4; ++e4) {
+        const u4v s4 = __builtin_amdgcn_raw_buffer_load_b128(sw_rsrc, (n + e4 * 4) * 4, 0, 0);
+        const u4v c4 = __builtin_amdgcn_raw_buffer_load_b128(ct_rsrc, (n + e4 * 4) * 4, 0, 0);
+        const u4v z4 = __builtin_amdgcn_raw_buffer_load_b128(zw_rsrc, (n + e4 * 4) * 4, 0, 0);
 #pragma unroll
-    for (int pass = 0; pass < NPASS; ++pass) {
-      const int64_t t = m0 + pass * RPP + rr;
-      rt[pass] = a.rowterm[t < a.M ? t : a.M - 1];
+        for (int k = 0; k < 4; ++k) {
+          sw[e4 * 4 + k] = __uint_as_float(s4[k]);
+          ct[e4 * 4 + k] = __uint_as_float(c4[k]);
+          zw[e4 * 4 + k] = static_cast<float>(static_cast<int32_t>(z4[k]));
+        }
+      }
+#pragma unroll
+      for (int pass = 0; pass < NPASS; ++pass)
+        rt[pass] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rt_rsrc, (pass * RPP + rr) * 4, 0, 0));
     }
     __syncthreads();                                        // every wave is done with the pipeline buffers
 #pragma unroll
