@@ -70,21 +70,43 @@ def main():
     t_setup = time.time()
     sites = []
     host_sites = []
+    # pass 1: inputs and calibration of every site.  A site without LayerNorm is the ReLU site
+    # of an FFN: its input is the output of the first linear layer of the site before it, and it
+    # is calibrated on that layer's output in the unquantized model (torch fp32, set-up only).
     for si, spec in enumerate(cfg.sites):
-        if not spec.layernorm:
-            raise SystemExit("bench.py: config %d chains a ReLU site; not a bench workload yet" % args.config)
         seed = w.site_seed(args.config, si)
-        site = w.make_site(seed, spec.d, M, cfg.n_cal)
-        gamma, beta = torch.from_numpy(site.gamma).cuda(), torch.from_numpy(site.beta).cuda()
-        cal = rp.calibrate_site([dev_bf16(b) for b in site.cal], gamma, beta, EPS, False, spec.g, bits, seed=seed)
-        xs = [dev_bf16(site.x)]
-        for k in range(1, args.sets):       # further batches from the same channel model
-            xs.append(dev_bf16(w.extra_batch(site, k, M)))
+        if spec.layernorm:
+            site = w.make_site(seed, spec.d, M, cfg.n_cal)
+            gamma, beta = torch.from_numpy(site.gamma).cuda(), torch.from_numpy(site.beta).cuda()
+            cal = rp.calibrate_site([dev_bf16(b) for b in site.cal], gamma, beta, EPS, False, spec.g, bits, seed=seed)
+            xs = [dev_bf16(site.x)]
+            for k in range(1, args.sets):       # further batches from the same channel model
+                xs.append(dev_bf16(w.extra_batch(site, k, M)))
+            Ws = [w.weight_matrix(seed + 500 + li, N, spec.d) for li, (_, N) in enumerate(spec.gemms)]
+            sites.append(dict(spec=spec, cal=cal, run_cal=cal, xs=xs, relu=False, perm_out=[None] * len(Ws)))
+            host_sites.append(dict(site=site, W=Ws))
+        else:
+            prev, hprev = sites[-1], host_sites[-1]
+            pg, pb = torch.from_numpy(hprev["site"].gamma).cuda(), torch.from_numpy(hprev["site"].beta).cuda()
+            W1 = torch.from_numpy(hprev["W"][0]).cuda()
+            hcal = []
+            for bch in hprev["site"].cal:
+                xb = dev_bf16(bch).float()
+                hcal.append((torch.nn.functional.layer_norm(xb, (xb.shape[1],), pg, pb, EPS) @ W1.T).to(torch.bfloat16))
+            del W1
+            cal = rp.calibrate_site(hcal, None, None, EPS, True, spec.g, bits, seed=seed)
+            del hcal
+            prev["perm_out"][0] = cal.perm_dev          # fc1's rows leave in this site's cluster order
+            Ws = [w.weight_matrix(seed + 500 + li, N, spec.d) for li, (_, N) in enumerate(spec.gemms)]
+            sites.append(dict(spec=spec, cal=cal, run_cal=rp.identity_site(cal), xs=None, relu=True,
+                              perm_out=[None] * len(Ws)))
+            host_sites.append(dict(site=None, W=Ws))
+    # pass 2: folding and buffers
+    for s, hs in zip(sites, host_sites):
+        spec, cal = s["spec"], s["cal"]
         lins = []
-        host_W = []
         for li, (lname, N) in enumerate(spec.gemms):
-            Wh = w.weight_matrix(seed + 500 + li, N, spec.d)
-            lin0 = rp.fold_linear(cal, torch.from_numpy(Wh).cuda())
+            lin0 = rp.fold_linear(cal, torch.from_numpy(hs["W"][li]).cuda(), perm_out=s["perm_out"][li])
             copies = [lin0]
             for k in range(1, args.sets):
                 c = rp.FoldedLinear(N=N, Wq=lin0.Wq.clone(), sW=lin0.sW.clone(), zW=lin0.zW.clone(),
@@ -92,26 +114,26 @@ def main():
                 copies.append(c)
             ys = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(min(2, args.sets))]
             lins.append(dict(name=lname, N=N, copies=copies, ys=ys))
-            host_W.append(Wh)
-        codes = torch.empty(rp.rptq_codes_bytes(M, cal.k_padded, bits), dtype=torch.uint8, device="cuda")
-        rowterm = torch.empty(M, dtype=torch.float32, device="cuda")
-        sites.append(dict(spec=spec, cal=cal, xs=xs, lins=lins, codes=codes, rowterm=rowterm))
-        host_sites.append(dict(site=site, W=host_W))
+        s["lins"] = lins
+        s["codes"] = torch.empty(rp.rptq_codes_bytes(M, cal.k_padded, bits), dtype=torch.uint8, device="cuda")
+        s["rowterm"] = torch.empty(M, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
     def step(i, events=None):
         k = i % args.sets
+        prev_y = None
         for si, s in enumerate(sites):
-            cal = s["cal"]
+            cal = s["run_cal"]
+            x = s["xs"][k] if s["xs"] is not None else prev_y
             if events is not None:
                 e0 = torch.cuda.Event(enable_timing=True); e0.record()
-            rp.rptq_ln_quant(s["xs"][k], M, cal.d, cal.gamma_pad, cal.beta_pad, EPS, False, cal.perm_pad,
+            rp.rptq_ln_quant(x, M, cal.d, cal.gamma_pad, cal.beta_pad, EPS, s["relu"], cal.perm_pad,
                              cal.cluster_off, cal.s, cal.inv_s, cal.z, bits, s["codes"], None, s["rowterm"])
             if events is not None:
                 e1 = torch.cuda.Event(enable_timing=True); e1.record()
                 events.append(("ln_quant:%s" % s["spec"].name, e0, e1))
-            for lin in s["lins"]:
+            for li, lin in enumerate(s["lins"]):
                 c = lin["copies"][k]
                 y = lin["ys"][i % len(lin["ys"])]
                 if events is not None:
@@ -121,6 +143,8 @@ def main():
                 if events is not None:
                     e1 = torch.cuda.Event(enable_timing=True); e1.record()
                     events.append(("gemm:%s" % lin["name"], e0, e1))
+                if li == 0:
+                    prev_y = y
 
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda")
@@ -211,15 +235,23 @@ def main():
         budget_flops = 4e11                       # keeps the leg to roughly 10-30 s of CPU work
         flops_per_row = sum(2.0 * N * s["spec"].d for s in sites for (_, N) in s["spec"].gemms)
         rows = int(max(16, min(M, budget_flops // flops_per_row)))
-        wqs = [[o.quantize_weights(Wh, s["cal"].perm) for Wh in hs["W"]]          # offline work, untimed
-               for s, hs in zip(sites, host_sites)]
+        # the oracle keeps the per-cluster integers [g, rows, N] (int64): bound that array to about 2 GB
+        rows = int(max(16, min(rows, 2e9 // (8 * max(s["spec"].g * N for s in sites for (_, N) in s["spec"].gemms)))))
+        wqs = [[o.quantize_weights(Wh, s["cal"].perm, None if po is None else po.cpu().numpy())          # offline work, untimed
+                for Wh, po in zip(hs["W"], s["perm_out"])] for s, hs in zip(sites, host_sites)]
         tc = time.perf_counter()
+        hidden = None
         for s, hs, wl in zip(sites, host_sites, wqs):
             cal = s["cal"]
-            codes, xsum, _ = o.ln_quant(hs["site"].x[:rows], hs["site"].gamma, hs["site"].beta, EPS, False,
-                                        cal.perm, cal.cluster_off, cal.inv_s, cal.z, bits)
-            for wq, sW, _, zW in wl:
-                o.cluster_gemm_int(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+            if s["relu"]:        # input already in this site's cluster order (fc1's rows were permuted offline)
+                codes, xsum, _ = o.ln_quant(hidden, None, None, EPS, True, None, cal.cluster_off, cal.inv_s, cal.z, bits)
+            else:
+                codes, xsum, _ = o.ln_quant(hs["site"].x[:rows], hs["site"].gamma, hs["site"].beta, EPS, False,
+                                            cal.perm, cal.cluster_off, cal.inv_s, cal.z, bits)
+            for li, (wq, sW, _, zW) in enumerate(wl):
+                _, _, Y = o.cluster_gemm_int(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+                if li == 0:
+                    hidden = w.round_to_bf16(Y.astype(np.float32))
         online = max(time.perf_counter() - tc, 1e-9)
         cpu = dict(value=round(rows / online, 2), unit="tokens/s", cores=cores, kind="oracle",
                    sample="%d of %d tokens, all sites and GEMMs of the workload, numpy float64/int64 oracle "
