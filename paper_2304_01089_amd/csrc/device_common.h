@@ -64,8 +64,7 @@ __device__ __forceinline__ void row_stats(double s1, double s2, int d, float eps
   var = var < 0.0 ? 0.0 : var;
   const double x = var + static_cast<double>(eps);
   double y = __builtin_amdgcn_rsq(x);                           // about 2^-26 relative
-  y = y * fma(-0.5 * x * y, y, 1.5);
-  y = y * fma(-0.5 * x * y, y, 1.5);
+  y = y * fma(-0.5 * x * y, y, 1.5);                           // error about 1.5 e^2: 2^-51 after one step
   y = y * fma(-0.5 * x * y, y, 1.5);
   *mu32 = static_cast<float>(mu);
   *rstd32 = static_cast<float>(y);

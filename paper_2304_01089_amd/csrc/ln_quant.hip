@@ -90,40 +90,41 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   const int n_rows = static_cast<int>((a.M - row0 + stride - 1) / stride);   // >= 1: the grid has at most M workgroups
 
   // Sum of the unit threads' partials in a fixed order: per lane over the waves, then over the lanes.
-  auto finalize_stats = [&](int pb) {
-    double s1 = 0.0, s2 = 0.0;
-    const double* p = part12 + (static_cast<size_t>(pb) * TU + lane) * 2;
+  // One pass of the statistics wave: {S1, S2} of the row staged last (parity pb_stats) and the
+  // de-quantized sum of the row stored last (parity pb_rt) are reduced together, so that the
+  // three dependent chains overlap; fixed summation order (per lane over the unit waves, then
+  // over the lanes).
+  auto finalize = [&](bool do_stats, int pb_stats, bool do_rt, int pb_rt, int64_t rt_row) {
+    double s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    const double* p12 = part12 + (static_cast<size_t>(pb_stats) * TU + lane) * 2;
+    const double* p3 = part3 + static_cast<size_t>(pb_rt) * TU + lane;
     for (int j = 0; j < nwu; j += 4) {                            // four reads in flight; surplus slots re-read wave 0
       double2 v[4];
+      double r[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const double2*>(p + ((j + k) < nwu ? (j + k) : 0) * 128);
+      for (int k = 0; k < 4; ++k) {
+        const int jj = (j + k) < nwu ? (j + k) : 0;
+        v[k] = *reinterpret_cast<const double2*>(p12 + jj * 128);
+        r[k] = p3[jj * 64];
+      }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const bool in = (j + k) < nwu;
         s1 += in ? v[k].x : 0.0;
         s2 += in ? v[k].y : 0.0;
+        s3 += in ? r[k] : 0.0;
       }
     }
-    const double t1 = wave_sum(s1), t2 = wave_sum(s2);
-    float mu, rstd;
-    row_stats(t1, t2, a.d, a.eps, &mu, &rstd);
-    if (lane == 0) {
-      bcast[pb * 2 + 0] = mu;
-      bcast[pb * 2 + 1] = rstd;
+    const double t1 = wave_sum(s1), t2 = wave_sum(s2), t3 = wave_sum(s3);
+    if (LN && do_stats) {
+      float mu, rstd;
+      row_stats(t1, t2, a.d, a.eps, &mu, &rstd);
+      if (lane == 0) {
+        bcast[pb_stats * 2 + 0] = mu;
+        bcast[pb_stats * 2 + 1] = rstd;
+      }
     }
-  };
-  auto finalize_rowterm = [&](int pb, int64_t row) {
-    double s3 = 0.0;
-    const double* p = part3 + static_cast<size_t>(pb) * TU + lane;
-    for (int j = 0; j < nwu; j += 4) {
-      double v[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) v[k] = p[((j + k) < nwu ? (j + k) : 0) * 64];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) s3 += (j + k) < nwu ? v[k] : 0.0;
-    }
-    const double t3 = wave_sum(s3);
-    if (lane == 0 && a.rowterm) a.rowterm[row] = static_cast<float>(t3);
+    if (do_rt && lane == 0 && a.rowterm) a.rowterm[rt_row] = static_cast<float>(t3);
   };
 
   if (stats_wave) {
@@ -132,15 +133,14 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     // issues ahead of the unit waves that share its SIMD.
     __builtin_amdgcn_s_setprio(3);
     __syncthreads();                                           // row 0 staged
-    if (LN) finalize_stats(0);
+    finalize(true, 0, false, 0, 0);
     for (int i = 0; i < n_rows; ++i) {
       __syncthreads();                                         // row i+1 staged, row i-1 stored
-      if (LN) finalize_stats((i + 1) & 1);
-      if (i >= 1) finalize_rowterm((i - 1) & 1, row0 + (i - 1) * stride);
+      finalize(true, (i + 1) & 1, i >= 1, (i - 1) & 1, row0 + (i - 1) * stride);
       if (a.ring == 2) __syncthreads();
     }
     __syncthreads();
-    finalize_rowterm((n_rows - 1) & 1, row0 + (n_rows - 1) * stride);
+    finalize(false, 0, true, (n_rows - 1) & 1, row0 + (n_rows - 1) * stride);
     return;
   }
 
