@@ -6,7 +6,7 @@ workload: for every quantization site, LayerNorm-in-cluster-order + per-cluster
 quantization (one kernel), then the cluster-wise integer GEMM of every linear layer that
 reads the site.  Inputs are resident in HBM before the timed region.  Prints one JSON
 line: tokens/s of the whole step, the roofline record of the dominant kernel (measured
-with HIP events around its launches on the launch stream), and the CPU oracle timed on
+with HIP events around runs of its launches on the launch stream), and the CPU oracle timed on
 the host cores on the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu]
@@ -120,31 +120,28 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
-    def step(i, events=None):
-        k = i % args.sets
-        prev_y = None
-        for si, s in enumerate(sites):
-            cal = s["run_cal"]
-            x = s["xs"][k] if s["xs"] is not None else prev_y
-            if events is not None:
-                e0 = torch.cuda.Event(enable_timing=True); e0.record()
+    # the launches of one step, in order: (stage name, launch(i)) with i the step index
+    launches = []
+    prev_ys = None
+    for s in sites:
+        cal = s["run_cal"]
+
+        def ln_launch(i, s=s, cal=cal, prev_ys=prev_ys):
+            x = s["xs"][i % args.sets] if s["xs"] is not None else prev_ys[i % len(prev_ys)]
             rp.rptq_ln_quant(x, M, cal.d, cal.gamma_pad, cal.beta_pad, EPS, s["relu"], cal.perm_pad,
                              cal.cluster_off, cal.s, cal.inv_s, cal.z, bits, s["codes"], None, s["rowterm"])
-            if events is not None:
-                e1 = torch.cuda.Event(enable_timing=True); e1.record()
-                events.append(("ln_quant:%s" % s["spec"].name, e0, e1))
-            for li, lin in enumerate(s["lins"]):
-                c = lin["copies"][k]
-                y = lin["ys"][i % len(lin["ys"])]
-                if events is not None:
-                    e0 = torch.cuda.Event(enable_timing=True); e0.record()
+        launches.append(("ln_quant:%s" % s["spec"].name, ln_launch))
+        for lin in s["lins"]:
+            def gemm_launch(i, s=s, cal=cal, lin=lin):
+                c = lin["copies"][i % args.sets]
                 rp.rptq_cluster_gemm(s["codes"], M, bits, c.Wq, c.N, cal.cluster_off, cal.s, c.sW, c.zW, c.colterm,
-                                     s["rowterm"], y)
-                if events is not None:
-                    e1 = torch.cuda.Event(enable_timing=True); e1.record()
-                    events.append(("gemm:%s" % lin["name"], e0, e1))
-                if li == 0:
-                    prev_y = y
+                                     s["rowterm"], lin["ys"][i % len(lin["ys"])])
+            launches.append(("gemm:%s" % lin["name"], gemm_launch))
+        prev_ys = s["lins"][0]["ys"]
+
+    def step(i):
+        for _, fn in launches:
+            fn(i)
 
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda")
@@ -172,19 +169,30 @@ def main():
     ms_per_step = t0.elapsed_time(t1) / args.steps
     tokens_per_s = M / (ms_per_step * 1e-3)
 
-    # ---- per-kernel durations over the same K steps (HIP events around each launch) ------------
-    import gc
-    events = []
-    gc.disable()
-    for i in range(args.steps):
-        step(i, events)
-    torch.cuda.synchronize()
-    gc.enable()
+    # ---- per-kernel durations: HIP events around runs of R launches of one stage (the same launch
+    # arguments and rotating input sets as in the steps; about K launches per stage in all).  Events
+    # around single launches would add the gaps between dispatches to kernels this short.
+    R = 20
+    blocks = max(3, args.steps // R)
     stage_ms = {}
-    for name, e0, e1 in events:
-        stage_ms.setdefault(name, []).append(e0.elapsed_time(e1))
-    # An event pair also spans any host-side stall between its two records (the launch sits
-    # between them); such samples are far outside the kernel's duration and are dropped.
+    for name, fn in launches:
+        for i in range(5):
+            fn(i)
+        torch.cuda.synchronize()
+        evs = []
+        for bi in range(blocks):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            for i in range(5):          # keeps the GPU busy while the host queues the run behind it:
+                step(i)                 # the run is then paced by the kernel, not by launch overhead
+            e0.record()
+            for i in range(R):
+                fn(bi * R + i)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        stage_ms[name] = [e0.elapsed_time(e1) / R for e0, e1 in evs]
+    # (a block that met a host-side stall is far outside the others and is dropped)
     def robust_mean(v):
         v = np.asarray(v, dtype=np.float64)
         return float(v[v <= 3.0 * np.median(v)].mean())
