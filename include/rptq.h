@@ -159,6 +159,10 @@ int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
  *  xsum       device int32 [M,g] out or NULL: per-cluster code sums
  *  rowterm    device fp32 [M] out or NULL: sum_i s_i (xsum[t,i] - n_i z_i), the row sum of
  *             the de-quantized activation, which the product's zero-point term needs
+ * Shapes the kernel does not cover return RPTQ_ERR_SHAPE before anything is launched: a
+ * workgroup holds at most 960 unit threads of at most 2 (LayerNorm; 1 at 3 bits) or 4 (2)
+ * units of 8 (16) codes, i.e. K_p <= 15360 with LayerNorm and K_p <= 30720 without, and two
+ * bf16 copies of a row plus the partial sums must fit the 160 KiB of LDS.
  */
 int32_t rptq_ln_quant(const void* x, int64_t M, int32_t d,
                       const float* gamma_pad, const float* beta_pad, float eps, int32_t relu,

@@ -71,6 +71,9 @@ def test_validation_happens_before_any_device_work(lib):
     assert lib.rptq_ln_quant(vp(4100), 4, 64, None, None, 1e-5, 0, dummy, off, 1, one, one, zero, 4, dummy, None, None, None) == -4
     big = (i32 * 1)(1 << 22)
     assert lib.rptq_ln_quant(dummy, 4, 64, None, None, 1e-5, 0, dummy, off, 1, one, one, big, 4, dummy, None, None, None) == -6
+    # a LayerNorm row wider than one workgroup covers (K_p > 15360) is refused before any launch
+    wide = (i32 * 2)(0, 16384)
+    assert lib.rptq_ln_quant(dummy, 4, 16384, dummy, dummy, 1e-5, 0, dummy, wide, 1, one, one, zero, 4, dummy, None, None, None) == -2
     assert lib.rptq_cluster_gemm(dummy, 4, 4, dummy, 8, off, 1, one, dummy, dummy, dummy, None, dummy, 1, None) == -1
     assert lib.rptq_cluster_gemm(dummy, 4, 4, dummy, 0, off, 1, one, dummy, dummy, dummy, dummy, dummy, 1, None) == -2
     perm = (i32 * 4)(0, 1, 1, 3)
