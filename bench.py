@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: OPT-1.3b layer)")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/weight copies cycled through the steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--fuse-next-site", action="store_true",
+                    help="chained workloads: quantize for the next site in fc1's output stage "
+                         "(rptq_cluster_gemm_quant) instead of storing fc1's bf16 output and quantizing it "
+                         "with a second kernel")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to scale profiler byte counters)")
     return ap.parse_args()
@@ -96,7 +100,11 @@ def main():
             del W1
             cal = rp.calibrate_site(hcal, None, None, EPS, True, spec.g, bits, seed=seed)
             del hcal
-            prev["perm_out"][0] = cal.perm_dev          # fc1's rows leave in this site's cluster order
+            prev["row_perm_host"] = cal.perm
+            if not args.fuse_next_site:
+                prev["perm_out"][0] = cal.perm_dev      # fc1's rows leave in this site's cluster order
+            else:
+                prev["next_site"] = cal                 # ... and padded like it: fc1's output stage quantizes
             Ws = [w.weight_matrix(seed + 500 + li, N, spec.d) for li, (_, N) in enumerate(spec.gemms)]
             sites.append(dict(spec=spec, cal=cal, run_cal=rp.identity_site(cal), xs=None, relu=True,
                               perm_out=[None] * len(Ws)))
@@ -106,14 +114,20 @@ def main():
         spec, cal = s["spec"], s["cal"]
         lins = []
         for li, (lname, N) in enumerate(spec.gemms):
-            lin0 = rp.fold_linear(cal, torch.from_numpy(hs["W"][li]).cuda(), perm_out=s["perm_out"][li])
+            nxt = s.get("next_site") if li == 0 else None
+            lin0 = rp.fold_linear(cal, torch.from_numpy(hs["W"][li]).cuda(), perm_out=s["perm_out"][li], next_site=nxt)
             copies = [lin0]
             for k in range(1, args.sets):
-                c = rp.FoldedLinear(N=N, Wq=lin0.Wq.clone(), sW=lin0.sW.clone(), zW=lin0.zW.clone(),
+                c = rp.FoldedLinear(N=lin0.N, Wq=lin0.Wq.clone(), sW=lin0.sW.clone(), zW=lin0.zW.clone(),
                                     wsum=lin0.wsum, colterm=lin0.colterm.clone())
                 copies.append(c)
-            ys = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(min(2, args.sets))]
-            lins.append(dict(name=lname, N=N, copies=copies, ys=ys))
+            if nxt is None:
+                ys = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(min(2, args.sets))]
+                ws = None
+            else:
+                ys = None
+                ws = torch.empty(rp.rptq_cluster_gemm_quant_workspace_bytes(M, lin0.N), dtype=torch.uint8, device="cuda")
+            lins.append(dict(name=lname, N=N, copies=copies, ys=ys, next_site=nxt, workspace=ws))
         s["lins"] = lins
         s["codes"] = torch.empty(rp.rptq_codes_bytes(M, cal.k_padded, bits), dtype=torch.uint8, device="cuda")
         s["rowterm"] = torch.empty(M, dtype=torch.float32, device="cuda")
@@ -123,15 +137,28 @@ def main():
     # the launches of one step, in order: (stage name, launch(i)) with i the step index
     launches = []
     prev_ys = None
-    for s in sites:
+    fed_by_gemm = False                      # this site's codes are written by the previous product's output stage
+    for si, s in enumerate(sites):
         cal = s["run_cal"]
 
         def ln_launch(i, s=s, cal=cal, prev_ys=prev_ys):
             x = s["xs"][i % args.sets] if s["xs"] is not None else prev_ys[i % len(prev_ys)]
             rp.rptq_ln_quant(x, M, cal.d, cal.gamma_pad, cal.beta_pad, EPS, s["relu"], cal.perm_pad,
                              cal.cluster_off, cal.s, cal.inv_s, cal.z, bits, s["codes"], None, s["rowterm"])
-        launches.append(("ln_quant:%s" % s["spec"].name, ln_launch))
+        if not fed_by_gemm:
+            launches.append(("ln_quant:%s" % s["spec"].name, ln_launch))
+        fed_by_gemm = False
         for lin in s["lins"]:
+            if lin["next_site"] is not None:
+                def gemm_launch(i, s=s, cal=cal, lin=lin, nxt=sites[si + 1]):
+                    c, nc = lin["copies"][i % args.sets], lin["next_site"]
+                    rp.rptq_cluster_gemm_quant(s["codes"], M, bits, c.Wq, c.N, cal.cluster_off, cal.s, c.sW, c.zW,
+                                               c.colterm, s["rowterm"], True, nc.cluster_off, nc.s, nc.inv_s, nc.z,
+                                               nc.bits, nxt["codes"], nxt["rowterm"], lin["workspace"])
+                launches.append(("gemm_quant:%s" % lin["name"], gemm_launch))
+                fed_by_gemm = True
+                continue
+
             def gemm_launch(i, s=s, cal=cal, lin=lin):
                 c = lin["copies"][i % args.sets]
                 rp.rptq_cluster_gemm(s["codes"], M, bits, c.Wq, c.N, cal.cluster_off, cal.s, c.sW, c.zW, c.colterm,
@@ -206,6 +233,10 @@ def main():
         alg_bytes = M * (2 * d + d * bits / 8.0)
         stage_info[name] = dict(bound="hbm", work=alg_bytes, unit="GB/s", peak=PEAK_HBM_GBS, scale=1e-9)
         for lin in s["lins"]:
+            if lin["next_site"] is not None:        # same product; the next site's quantizer rides in its output stage
+                ops = 2.0 * M * lin["N"] * d
+                stage_info["gemm_quant:%s" % lin["name"]] = dict(bound="mfma", work=ops, unit="TOP/s", peak=PEAK_INT8_TOPS, scale=1e-12)
+                continue
             if M <= 32:
                 # decode: the packed weights are streamed once; judged against HBM (unpadded algorithmic bytes)
                 by = lin["N"] * d / 2.0 + M * d * bits / 8.0 + M * lin["N"] * 2.0
@@ -245,8 +276,8 @@ def main():
         rows = int(max(16, min(M, budget_flops // flops_per_row)))
         # the oracle keeps the per-cluster integers [g, rows, N] (int64): bound that array to about 2 GB
         rows = int(max(16, min(rows, 2e9 // (8 * max(s["spec"].g * N for s in sites for (_, N) in s["spec"].gemms)))))
-        wqs = [[o.quantize_weights(Wh, s["cal"].perm, None if po is None else po.cpu().numpy())          # offline work, untimed
-                for Wh, po in zip(hs["W"], s["perm_out"])] for s, hs in zip(sites, host_sites)]
+        wqs = [[o.quantize_weights(Wh, s["cal"].perm, s.get("row_perm_host") if li == 0 else None)      # offline work, untimed
+                for li, Wh in enumerate(hs["W"])] for s, hs in zip(sites, host_sites)]
         tc = time.perf_counter()
         hidden = None
         for s, hs, wl in zip(sites, host_sites, wqs):
@@ -282,7 +313,8 @@ def main():
             args.config, cfg.name, M, bits,
             ";".join("%s(d=%d,g=%d)->%s" % (s.name, s.d, s.g, ",".join("%s %dx%d" % (n, N, s.d) for n, N in s.gemms))
                      for s in cfg.sites)),
-            "input_sets": args.sets, "y_dtype": "bf16", "setup_s": round(t_setup, 2)},
+            "input_sets": args.sets, "y_dtype": "bf16", "setup_s": round(t_setup, 2),
+            "next_site_quantized_in_output_stage": any(l["next_site"] is not None for s in sites for l in s["lins"])},
         "roofline": roofline,
         "stages": stages,
         "cpu_baseline": cpu,

@@ -129,7 +129,10 @@ int32_t rptq_calibrate(const void* const* x_batches, const int64_t* rows, int32_
  *             supplied in perm_in_host, host int32 [K])
  *  cluster_off,sX,zX  host [g+1],[g],[g]: the site's calibration result
  *  W          device [N,K] row-major, w_dtype RPTQ_DTYPE_BF16 or RPTQ_DTYPE_F32
- *  perm_out   device int32 [N] or NULL; output row o' is original row perm_out[o']
+ *  perm_out   device int32 [N] or NULL; output row o' is original row perm_out[o'];
+ *             -1 makes o' a pad row (weights 0, sW = 1, zW = 0, so Y[:,o'] = 0).  Passing the
+ *             *next* site's perm_pad with N = its K_p lays the product's columns out as that
+ *             site's padded cluster-order positions (what rptq_cluster_gemm_quant needs).
  *  perm_pad   device int32 [K_p] out: source channel of each padded position, -1 = pad
  *  gamma_pad,beta_pad device fp32 [K_p] out (untouched when gamma == NULL)
  *  Wq_packed  device out, rptq_weight_bytes(N, K_p)
@@ -188,6 +191,35 @@ int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
                           const float* sX, const float* sW, const int32_t* zW,
                           const float* colterm, const float* rowterm,
                           void* y, int32_t y_dtype, void* stream);
+
+/* ---- stage 3 with the next site's quantizer as its output stage (Sec. 4.2; Eq. 1) ------
+ * For a linear layer whose output feeds another quantized site (fc1 -> ReLU -> fc2): the
+ * layer's rows were reordered offline into the next site's padded cluster order (perm_out
+ * of rptq_fold_reorder = that site's perm_pad, N = its K_p), so the product leaves the
+ * matrix cores already in that order and is quantized in place of being stored:
+ *     h = bf16(Y[t,n])  (the value rptq_cluster_gemm would have stored; round to nearest even)
+ *     q = clamp(round(max(h,0) * inv_s_i) + z_i, ...)   i = next site's cluster of position n
+ * exactly as rptq_ln_quant without LayerNorm does on a stored bf16 Y; pad positions get
+ * code 0.  The bf16 tensor between the two layers is never written or read.
+ *
+ *  first twelve arguments: as rptq_cluster_gemm; N must equal the next site's K_p
+ *  relu       != 0: max(h,0) before quantizing
+ *  next_*     host: the next site's cluster_off [next_g+1], s, inv_s, z [next_g]; next_bits in {4,8}
+ *             (RPTQ_ERR_BITS otherwise)
+ *  next_codes device out, rptq_codes_bytes(M, N, next_bits)
+ *  next_rowterm device fp32 [M] out: as rptq_ln_quant's rowterm, for the next product
+ *  workspace  device, rptq_cluster_gemm_quant_workspace_bytes(M, N) (RPTQ_ERR_WORKSPACE if
+ *             smaller); holds per-column-tile row sums between the two kernels of this call
+ */
+size_t rptq_cluster_gemm_quant_workspace_bytes(int64_t M, int32_t N);
+int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bits,
+                                const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                const float* sX, const float* sW, const int32_t* zW,
+                                const float* colterm, const float* rowterm, int32_t relu,
+                                const int32_t* next_cluster_off, int32_t next_g, const float* next_s,
+                                const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
+                                void* next_codes, float* next_rowterm,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- helpers for verification (not on the timed path) ---------------------------- */
 

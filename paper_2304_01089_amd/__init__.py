@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     rptq_fold_reorder,
     rptq_ln_quant,
     rptq_cluster_gemm,
+    rptq_cluster_gemm_quant,
+    rptq_cluster_gemm_quant_workspace_bytes,
     rptq_cluster_gemm_partials,
     rptq_unpack_codes,
     rptq_unpack_weights,
@@ -28,4 +30,4 @@ from .binding import (  # noqa: F401
     DTYPE_BF16,
     DTYPE_F32,
 )
-from .layer import Calibration, FoldedLinear, calibrate_site, identity_site, fold_linear, ln_quant, cluster_gemm  # noqa: F401
+from .layer import Calibration, FoldedLinear, calibrate_site, identity_site, fold_linear, ln_quant, cluster_gemm, cluster_gemm_quant  # noqa: F401

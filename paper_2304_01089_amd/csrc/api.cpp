@@ -4,6 +4,7 @@
 #include <vector>
 
 #include "rptq_internal.h"
+#include "gemm_common.h"
 
 using namespace rptq;
 
@@ -158,7 +159,56 @@ int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
       !aligned16(rowterm) || !aligned16(y))
     return RPTQ_ERR_ALIGN;
   return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, sX, sW, zW, colterm, rowterm, y, y_dtype, nullptr,
-                     nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                     nullptr, nullptr, nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+size_t rptq_cluster_gemm_quant_workspace_bytes(int64_t M, int32_t N) {
+  if (M < 0 || N < 1) return 0;
+  return gemm_quant_workspace_bytes(M, N);
+}
+
+int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bits,
+                                const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                const float* sX, const float* sW, const int32_t* zW,
+                                const float* colterm, const float* rowterm, int32_t relu,
+                                const int32_t* next_cluster_off, int32_t next_g, const float* next_s,
+                                const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
+                                void* next_codes, float* next_rowterm,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  if (!codes_packed || !Wq_packed || !sX || !sW || !zW || !colterm || !rowterm) return RPTQ_ERR_NULL;
+  if (!next_s || !next_inv_s || !next_z || !next_codes || !next_rowterm || !workspace) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  if (next_bits != 4 && next_bits != 8) return RPTQ_ERR_BITS;
+  ClusterGeom geom, next;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (int32_t st = check_clusters(next_cluster_off, next_g, &next)) return st;
+  // the product's columns are the padded positions of the next site's layout
+  if (M < 0 || N < 1 || N != next.k_padded) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i)
+    if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
+  QuantTab qt;
+  if (int32_t st = make_quant_tab(next, next_s, next_inv_s, next_z, next_bits, &qt)) return st;
+  if (workspace_bytes < gemm_quant_workspace_bytes(M, N)) return RPTQ_ERR_WORKSPACE;
+  if (!aligned16(codes_packed) || !aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) || !aligned16(colterm) ||
+      !aligned16(rowterm) || !aligned16(next_codes) || !aligned16(next_rowterm) || !aligned16(workspace))
+    return RPTQ_ERR_ALIGN;
+  GemmQuantOut qo = {};
+  qo.codes = static_cast<uint8_t*>(next_codes);
+  qo.rt_part = static_cast<double*>(workspace);
+  qo.row_bytes = N * next_bits / 8;
+  qo.relu = relu;
+  qo.g = next.g;
+  for (int i = 0; i <= RPTQ_MAX_CLUSTERS; ++i) qo.pad_off[i] = next.pad_off[i <= next.g ? i : next.g];
+  for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i) {
+    qo.n[i] = i < next.g ? next.off[i + 1] - next.off[i] : 0;
+    qo.inv_s[i] = qt.inv_s[i];
+    qo.s[i] = qt.s[i];
+    qo.z[i] = qt.z[i];
+    qo.zb[i] = qt.zb[i];
+  }
+  return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, sX, sW, zW, colterm, rowterm, nullptr,
+                     RPTQ_DTYPE_BF16, nullptr, nullptr, nullptr, nullptr, &qo, next_rowterm,
+                     static_cast<hipStream_t>(stream));
 }
 
 int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t bits,
@@ -176,7 +226,7 @@ int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t 
       !aligned16(yq))
     return RPTQ_ERR_ALIGN;
   return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, nullptr, nullptr, zW, nullptr, nullptr, nullptr,
-                     RPTQ_DTYPE_F32, zX, xsum, wsum, yq, static_cast<hipStream_t>(stream));
+                     RPTQ_DTYPE_F32, zX, xsum, wsum, yq, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int32_t rptq_unpack_codes(const void* codes_packed, int64_t rows, const int32_t* cluster_off, int32_t g,

@@ -68,6 +68,17 @@ __global__ void __launch_bounds__(256) fold_weight_kernel(FoldArgs a, ClusterGeo
     return;
   }
   const int64_t src_row = a.perm_out ? a.perm_out[o] : o;
+  if (src_row < 0) {                               // a pad row of the output layout: weights 0, s = 1, z = 0
+    for (int u = tid; u < n_units; u += blockDim.x)
+      *reinterpret_cast<uint32_t*>(a.Wq + weight_dword_offset(o, u, geom.k_padded)) = 0u;
+    if (tid < geom.g) a.wsum[static_cast<int64_t>(o) * geom.g + tid] = 0;
+    if (tid == 0) {
+      a.sW[o] = 1.0f;
+      a.zW[o] = 0;
+      a.colterm[o] = 0.0f;
+    }
+    return;
+  }
   const uint16_t* wb = static_cast<const uint16_t*>(a.W) + src_row * geom.k;
   const float* wf = static_cast<const float*>(a.W) + src_row * geom.k;
   auto wval = [&](int c) -> float { return a.w_bf16 ? __uint_as_float(static_cast<uint32_t>(wb[c]) << 16) : wf[c]; };

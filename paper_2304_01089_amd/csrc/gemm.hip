@@ -44,8 +44,13 @@ __device__ __forceinline__ void unpack3(uint32_t x0, uint32_t x1, uint32_t x2, u
   hi->w = ((x1 << 6) & 0xc0c0c0c0u) | ((x2 << 4) & 0x20202020u);
 }
 
-template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, bool YF32>
-__global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTab tab) {
+// OUT: what the output stage writes - kOutBf16 / kOutF32: Y; 4 or 8: the next site's packed
+// codes of that many bits (ReLU optional) and the partial row sums its product needs.
+constexpr int kOutBf16 = 0, kOutF32 = 1;
+template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT>
+__global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTab tab, GemmQuantOut qo) {
+  constexpr bool YF32 = OUT == kOutF32;
+  constexpr bool QOUT = OUT >= 2;
   constexpr int BM = WGM * WM * 32;
   constexpr int BN = WGN * WN * 32;
   constexpr int A_SLICE = 2 * BM * 16 + kSlicePad;       // [half][row][16 B]
@@ -378,6 +383,32 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       for (int pass = 0; pass < NPASS; ++pass)
         rt[pass] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rt_rsrc, (pass * RPP + rr) * 4, 0, 0));
     }
+    // quantizing output stage: this thread's eight columns are one unit (8 codes) of the next
+    // site's layout and lie in one cluster; its constants, and which of the eight are padding
+    constexpr int QB = QOUT ? OUT : 8;                      // bits of the codes written
+    constexpr int kQMin = -(1 << (QB - 1));
+    constexpr float kUMax = static_cast<float>((1 << QB) - 1);
+    float q_inv_s = 0.0f, q_zbf = 0.0f, q_floor = 0.0f;
+    double q_s = 0.0;
+    int32_t q_fix = 0;
+    uint32_t q_keep[2] = {0xffffffffu, 0xffffffffu}, q_fill[2] = {0u, 0u};
+    if (QOUT) {
+      int ci = 0;
+      for (int i = 1; i < qo.g; ++i) ci += (n >= qo.pad_off[i]) ? 1 : 0;
+      q_inv_s = qo.inv_s[ci];
+      q_zbf = static_cast<float>(qo.zb[ci]);
+      q_s = static_cast<double>(qo.s[ci]);
+      q_floor = qo.relu ? 0.0f : -__builtin_huge_valf();
+      int n_real = qo.pad_off[ci] + qo.n[ci] - n;           // real channels among the eight
+      n_real = n_real < 0 ? 0 : (n_real > 8 ? 8 : n_real);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e >= n_real) {                                  // pad position: code 0 (biased byte = -qmin)
+          q_keep[e / 4] &= ~(0xffu << (8 * (e & 3)));
+          q_fill[e / 4] |= static_cast<uint32_t>(-kQMin) << (8 * (e & 3));
+        }
+      q_fix = 8 * kQMin - n_real * qo.z[ci];                // sum of biased bytes -> sum of (q - z) over real codes
+    }
     __syncthreads();                                        // every wave is done with the pipeline buffers
 #pragma unroll
     for (int i = 0; i < WM; ++i)
@@ -405,7 +436,47 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       }
 #pragma unroll
       for (int e = 0; e < CW; ++e) v[e] = sw[e] * ((v[e] - ct[e]) - zw[e] * rt[pass]);
-      if (t < a.M) {
+      if (QOUT) {
+        // The value the next site quantizes is the bf16 the plain output stage would have
+        // stored; from there on the arithmetic of the quantize-only kernel (Eq. 1): ReLU,
+        // multiply by 1/s, round half to even, add the zero point, clamp.
+        uint32_t D[2] = {0u, 0u};
+#pragma unroll
+        for (int e = 0; e < CW / 2; ++e) {
+          const f2 pr = {v[2 * e], v[2 * e + 1]};
+          const b2 cv = __builtin_convertvector(pr, b2);
+          const uint32_t w2 = *reinterpret_cast<const uint32_t*>(&cv);
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int c = 2 * e + h;
+            float y = __uint_as_float(h ? (w2 & 0xffff0000u) : (w2 << 16));
+            y = fmaxf(y, q_floor);
+            const float r = __fmul_rn(y, q_inv_s);
+            float b = __fadd_rn(rintf(r), q_zbf);
+            if (QB < 8) b = fminf(b, kUMax);                // the conversion saturates at 0 and 255
+            D[c / 4] = __builtin_amdgcn_cvt_pk_u8_f32(b, c & 3, D[c / 4]);
+          }
+        }
+        D[0] = (D[0] & q_keep[0]) | q_fill[0];
+        D[1] = (D[1] & q_keep[1]) | q_fill[1];
+        const uint32_t usum = __builtin_amdgcn_sad_u8(D[1], 0u, __builtin_amdgcn_sad_u8(D[0], 0u, 0u));
+        const bool live = t < a.M && n < a.N;
+        double part = live ? q_s * static_cast<double>(static_cast<int32_t>(usum) + q_fix) : 0.0;
+        if (live) {
+          if (QB == 8) {
+            uint2 o;
+            o.x = D[0] ^ 0x80808080u;
+            o.y = D[1] ^ 0x80808080u;
+            *reinterpret_cast<uint2*>(qo.codes + t * qo.row_bytes + n) = o;
+          } else {
+            *reinterpret_cast<uint32_t*>(qo.codes + t * qo.row_bytes + (n >> 1)) = ((D[0] << 4) | D[1]) ^ 0x88888888u;
+          }
+        }
+        // the row's share of this column tile: sum over the CPR lanes that hold the row
+#pragma unroll
+        for (int m = CPR / 2; m >= 1; m >>= 1) part += __shfl_xor(part, m, kWave);
+        if (cc == 0 && t < a.M) qo.rt_part[static_cast<int64_t>(lin / tiles_m) * a.M + t] = part;
+      } else if (t < a.M) {
         if (YF32) {
           if (vec_ok) {
             *reinterpret_cast<float4*>(ybase + (t * a.N + n) * 4) = make_float4(v[0], v[1], v[2], v[3]);
@@ -435,43 +506,72 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   }
 }
 
+// Sum over the column tiles, in tile order, of the row sums the quantizing output stage left.
+__global__ void __launch_bounds__(256) rowterm_reduce_kernel(const double* part, int tiles_n, int64_t M, float* rowterm) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (t >= M) return;
+  double acc = 0.0;
+  for (int j = 0; j < tiles_n; ++j) acc += part[static_cast<int64_t>(j) * M + t];
+  rowterm[t] = static_cast<float>(acc);
+}
+
 // ---------------------------------------------------------------------------------------------
-template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, bool YF32>
-static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, hipStream_t st) {
+template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT>
+static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuantOut& qo, float* q_rowterm, hipStream_t st) {
   constexpr int BM = WGM * WM * 32, BN = WGN * WN * 32;
   constexpr size_t pipe = 2 * kStepSlices * (2 * BM * 16 + kSlicePad);
   constexpr size_t stage = PARTIALS ? 0 : static_cast<size_t>(BM) * (BN + 4) * 4;   // fp32 output tile of the workgroup
   constexpr size_t shmem = pipe > stage ? pipe : stage;
-  auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, YF32>;
+  auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, OUT>;
   if (shmem > 64 * 1024) RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
   GemmArgs b = a;
   b.tiles_n = (a.N + BN - 1) / BN;
   b.tiles_m = static_cast<int32_t>((a.M + BM - 1) / BM);
   const dim3 grid(static_cast<unsigned>(b.tiles_n) * static_cast<unsigned>(b.tiles_m));
-  hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab);
+  hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab, qo);
   RPTQ_HIP(hipGetLastError());
+  if (OUT >= 2) {
+    hipLaunchKernelGGL(rowterm_reduce_kernel, dim3(static_cast<unsigned>((a.M + 255) / 256)), dim3(256), 0, st,
+                       qo.rt_part, b.tiles_n, a.M, q_rowterm);
+    RPTQ_HIP(hipGetLastError());
+  }
   return RPTQ_OK;
 }
 
-template <int BITS, bool PARTIALS, bool YF32>
-static int32_t launch_shape(const GemmArgs& a, const GemmTab& tab, hipStream_t st) {
-  if (a.M <= 32) return launch_cfg<BITS, 1, 4, 1, 1, PARTIALS, YF32>(a, tab, st);
-  // 128 x 128 tile; every wave covers all 128 tokens and 32 output channels: each expanded
-  // weight fragment feeds four MFMAs and no two waves expand the same weights
-  return launch_cfg<BITS, 1, 4, 2, 2, PARTIALS, YF32>(a, tab, st);
+template <int BITS, bool PARTIALS, int OUT>
+static int32_t launch_shape(const GemmArgs& a, const GemmTab& tab, const GemmQuantOut& qo, float* q_rowterm, hipStream_t st) {
+  if (a.M <= 32) return launch_cfg<BITS, 1, 4, 1, 1, PARTIALS, OUT>(a, tab, qo, q_rowterm, st);
+  // 64 x 256 tile; every wave covers all 64 tokens and 64 output channels: each expanded
+  // weight fragment feeds two MFMAs and no two waves expand the same weights
+  return launch_cfg<BITS, 1, 4, 2, 2, PARTIALS, OUT>(a, tab, qo, q_rowterm, st);
 }
 
+// out_mode: -1 partial sums, kOutBf16, kOutF32, or the next site's code bits (4, 8)
 template <int BITS>
-static int32_t launch_bits(const GemmArgs& a, const GemmTab& tab, bool partials, bool yf32, hipStream_t st) {
-  if (partials) return launch_shape<BITS, true, true>(a, tab, st);
-  if (yf32) return launch_shape<BITS, false, true>(a, tab, st);
-  return launch_shape<BITS, false, false>(a, tab, st);
+static int32_t launch_bits(const GemmArgs& a, const GemmTab& tab, int out_mode, const GemmQuantOut& qo, float* q_rowterm,
+                           hipStream_t st) {
+  switch (out_mode) {
+    case -1: return launch_shape<BITS, true, kOutF32>(a, tab, qo, q_rowterm, st);
+    case kOutF32: return launch_shape<BITS, false, kOutF32>(a, tab, qo, q_rowterm, st);
+    case kOutBf16: return launch_shape<BITS, false, kOutBf16>(a, tab, qo, q_rowterm, st);
+    case 4: return launch_shape<BITS, false, 4>(a, tab, qo, q_rowterm, st);
+    case 8: return launch_shape<BITS, false, 8>(a, tab, qo, q_rowterm, st);
+  }
+  return RPTQ_ERR_BITS;
+}
+
+// Smallest column tile any launch shape uses: bounds the number of column tiles.
+constexpr int kMinTileN = 128;
+
+size_t gemm_quant_workspace_bytes(int64_t M, int32_t N) {
+  return static_cast<size_t>((N + kMinTileN - 1) / kMinTileN) * static_cast<size_t>(M) * sizeof(double);
 }
 
 int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, int32_t N,
                     const ClusterGeom& geom, const float* sX, const float* sW, const int32_t* zW,
                     const float* colterm, const float* rowterm, void* y, int32_t y_dtype,
-                    const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq, hipStream_t st) {
+                    const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
+                    const GemmQuantOut* quant_out, float* q_rowterm, hipStream_t st) {
   if (M == 0) return RPTQ_OK;
   GemmArgs a;
   a.codes = static_cast<const uint8_t*>(codes);
@@ -502,11 +602,16 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
     tab.zx[i] = (in && zX) ? zX[i] : 0;
     tab.n[i] = in ? geom.off[i + 1] - geom.off[i] : 0;
   }
-  const bool partials = yq != nullptr;
-  const bool yf32 = y_dtype == RPTQ_DTYPE_F32;
-  if (bits == 3) return launch_bits<3>(a, tab, partials, yf32, st);
-  if (bits == 4) return launch_bits<4>(a, tab, partials, yf32, st);
-  return launch_bits<8>(a, tab, partials, yf32, st);
+  GemmQuantOut qo = {};
+  int out_mode = (y_dtype == RPTQ_DTYPE_F32) ? kOutF32 : kOutBf16;
+  if (yq != nullptr) out_mode = -1;
+  if (quant_out != nullptr) {
+    qo = *quant_out;
+    out_mode = qo.row_bytes * 8 / N;                        // bits of the codes written
+  }
+  if (bits == 3) return launch_bits<3>(a, tab, out_mode, qo, q_rowterm, st);
+  if (bits == 4) return launch_bits<4>(a, tab, out_mode, qo, q_rowterm, st);
+  return launch_bits<8>(a, tab, out_mode, qo, q_rowterm, st);
 }
 
 }  // namespace rptq

@@ -38,6 +38,23 @@ struct GemmTab {
   int32_t n[RPTQ_MAX_CLUSTERS];           // channels in cluster i
 };
 
+// Output stage that quantizes for the next site instead of storing Y (Sec. 4.2: the rows of
+// this layer's weights were reordered offline, so column n of the product is padded position
+// n of the next site's cluster-order layout).  Passed by value; unused by the other kernels.
+struct GemmQuantOut {
+  uint8_t* codes;                          // packed codes of the next site, [M, N * bits / 8]
+  double* rt_part;                         // [tiles_n, M]: per column tile, the de-quantized row sum
+  int32_t row_bytes;                       // N * bits / 8
+  int32_t relu;
+  int32_t g;
+  int32_t pad_off[RPTQ_MAX_CLUSTERS + 1];  // padded start of the next site's clusters
+  int32_t n[RPTQ_MAX_CLUSTERS];            // channels in each
+  float inv_s[RPTQ_MAX_CLUSTERS];
+  float s[RPTQ_MAX_CLUSTERS];
+  int32_t z[RPTQ_MAX_CLUSTERS];
+  int32_t zb[RPTQ_MAX_CLUSTERS];           // z - qmin
+};
+
 constexpr int kStepSlices = 8;            // slices per K step (256 codes): one barrier per step
 constexpr int kSlicePad = 64;             // bytes added to a slice's LDS stride: 16 banks, so the four
                                           // slices a 16-lane write group touches fall in distinct banks

@@ -31,6 +31,8 @@ struct QuantTab {
   int32_t z[RPTQ_MAX_CLUSTERS];
 };
 
+struct GemmQuantOut;                       // gemm_common.h
+
 // Validation helpers (host.cpp).  All return an rptq_status.
 int32_t check_clusters(const int32_t* cluster_off, int32_t g, ClusterGeom* geom);
 int32_t check_bits(int32_t bits);
@@ -64,7 +66,9 @@ int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_
 int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, int32_t N,
                     const ClusterGeom& geom, const float* sX, const float* sW, const int32_t* zW,
                     const float* colterm, const float* rowterm, void* y, int32_t y_dtype,
-                    const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq, hipStream_t st);
+                    const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
+                    const GemmQuantOut* quant_out, float* q_rowterm, hipStream_t st);
+size_t gemm_quant_workspace_bytes(int64_t M, int32_t N);
 int32_t launch_unpack_codes(const void* codes, int64_t rows, const ClusterGeom& geom, int32_t bits, int8_t* out,
                             hipStream_t st);
 int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st);

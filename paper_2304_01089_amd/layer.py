@@ -75,9 +75,15 @@ def identity_site(cal: Calibration) -> Calibration:
     return out
 
 
-def fold_linear(cal: Calibration, W, perm_out=None) -> FoldedLinear:
+def fold_linear(cal: Calibration, W, perm_out=None, next_site: Optional[Calibration] = None) -> FoldedLinear:
+    """perm_out: reorder index of the layer's output (rows of W).  next_site: lay the rows out
+    as that site's padded cluster-order positions instead (pad rows are zero), which is what
+    cluster_gemm_quant needs; the layer then has next_site.k_padded outputs."""
     import torch
     N, K = W.shape
+    if next_site is not None:
+        perm_out = next_site.perm_pad
+        N = next_site.k_padded
     dev = W.device
     out = FoldedLinear(
         N=N,
@@ -113,3 +119,20 @@ def cluster_gemm(cal: Calibration, lin: FoldedLinear, codes, rowterm, M, y=None,
     B.rptq_cluster_gemm(codes, M, cal.bits, lin.Wq, lin.N, cal.cluster_off, cal.s, lin.sW, lin.zW, lin.colterm,
                         rowterm, y)
     return y
+
+
+def cluster_gemm_quant(cal: Calibration, lin: FoldedLinear, codes, rowterm, M, next_site: Calibration, relu=True,
+                       next_codes=None, next_rowterm=None, workspace=None):
+    """The product of `lin` (folded with next_site=...) quantized for `next_site` in the output stage."""
+    import torch
+    dev = codes.device
+    if next_codes is None:
+        next_codes = torch.empty(B.rptq_codes_bytes(M, next_site.k_padded, next_site.bits), dtype=torch.uint8, device=dev)
+    if next_rowterm is None:
+        next_rowterm = torch.empty(M, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(16, B.rptq_cluster_gemm_quant_workspace_bytes(M, lin.N)), dtype=torch.uint8, device=dev)
+    B.rptq_cluster_gemm_quant(codes, M, cal.bits, lin.Wq, lin.N, cal.cluster_off, cal.s, lin.sW, lin.zW, lin.colterm,
+                              rowterm, relu, next_site.cluster_off, next_site.s, next_site.inv_s, next_site.z,
+                              next_site.bits, next_codes, next_rowterm, workspace)
+    return next_codes, next_rowterm

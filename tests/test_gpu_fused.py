@@ -1,0 +1,143 @@
+"""The product whose output stage quantizes for the next site (fc1 -> ReLU -> quantize in
+fc2's cluster order, Sec. 4.2 + Eq. 1), against the oracle.
+
+The codes depend on the product's fp32 value through two rounding decisions (to bf16, then
+Eq. 1's round), so they are compared as follows: the oracle computes the product H in
+float64 from its own inputs; since bf16 rounding and the quantizer are both monotone, a
+code is valid iff it lies between the oracle's codes of H - tol and H + tol (tol = the
+product's own 1e-3 parity tolerance), and all but a small fraction must equal the oracle's
+code of H itself.  No device result is ever fed to the oracle."""
+import numpy as np
+import pytest
+
+import workloads as w
+from oracle import rptq_oracle as o
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+EPS = 1e-5
+
+
+@pytest.fixture(scope="module")
+def rp():
+    import paper_2304_01089_amd as rp_
+    rp_.load_library()
+    assert torch.cuda.is_available()
+    return rp_
+
+
+def dev_bf16(x):
+    return torch.from_numpy(w.bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def tol_of(Y):
+    return 1e-3 * np.maximum(np.abs(Y), np.sqrt((Y * Y).mean(axis=-1, keepdims=True)))
+
+
+def oracle_codes(H, relu, c2, bits):
+    """Eq. 1 on bf16(H) with site 2's clusters; H is already in site 2's cluster order."""
+    h = w.round_to_bf16(H.astype(np.float32))
+    rc, xs, _ = o.ln_quant(h, None, None, EPS, relu, None, c2.cluster_off, c2.inv_s, c2.z, bits)
+    return rc, xs
+
+
+@pytest.mark.parametrize("name,d,dff,M,bits,bits2,g,g2,relu", [
+    ("a4_to_a4", 256, 1024, 200, 4, 4, 8, 8, True),       # ragged rows, several column tiles
+    ("a4_to_a8", 256, 1000, 70, 4, 8, 8, 5, True),        # next site at 8 bits, odd cluster count
+    ("a8_to_a4_norelu", 128, 520, 64, 8, 4, 4, 8, False),
+    ("a3_to_a4", 256, 768, 130, 3, 4, 8, 8, True),
+    ("few_rows", 256, 1024, 20, 4, 4, 8, 8, True),        # the weight-streaming launch shape
+    ("one_row", 128, 256, 1, 4, 4, 4, 4, True),
+])
+def test_product_quantized_for_next_site(rp, name, d, dff, M, bits, bits2, g, g2, relu):
+    seed = 4100 + sum(map(ord, name))
+    site = w.make_site(seed, d, M, 4, 64)
+    W1 = w.weight_matrix(seed + 1, dff, d)
+    W2 = w.weight_matrix(seed + 2, d, dff)
+    c1 = o.calibrate(site.cal, site.gamma, site.beta, EPS, False, g, bits, seed=seed)
+
+    def fp_hidden(x):                                   # the unquantized model's hidden tensor (calibration input)
+        y, _ = o.layernorm_f32(x, site.gamma, site.beta, EPS)
+        return w.round_to_bf16((y.astype(np.float64) @ W1.astype(np.float64).T).astype(np.float32))
+    hcal = [fp_hidden(b) for b in site.cal]
+    c2 = o.calibrate(hcal, None, None, EPS, relu, g2, bits2, seed=seed + 1)
+
+    gamma, beta = torch.from_numpy(site.gamma).cuda(), torch.from_numpy(site.beta).cuda()
+    k1 = rp.calibrate_site([dev_bf16(b) for b in site.cal], gamma, beta, EPS, False, g, bits, seed=seed)
+    k2 = rp.calibrate_site([dev_bf16(h) for h in hcal], None, None, EPS, relu, g2, bits2, seed=seed + 1)
+    assert np.array_equal(k1.perm, c1.perm) and np.array_equal(k2.perm, c2.perm)
+    assert np.array_equal(k2.z, c2.z) and np.array_equal(k2.s, c2.s)
+
+    # fc1 laid out for the fused output stage: rows = site 2's padded positions
+    lin1q = rp.fold_linear(k1, torch.from_numpy(W1).cuda(), next_site=k2)
+    assert lin1q.N == k2.k_padded
+    codes1, _, rt1 = rp.ln_quant(k1, dev_bf16(site.x), EPS)
+    codes2, rt2 = rp.cluster_gemm_quant(k1, lin1q, codes1, rt1, M, k2, relu=relu)
+    got = torch.empty((M, dff), dtype=torch.int8, device="cuda")
+    rp.rptq_unpack_codes(codes2, M, k2.cluster_off, bits2, got)
+    got = got.cpu().numpy().astype(np.int64)
+
+    # oracle: its own codes, its own product, then the bracket
+    rc1, _, fr1 = o.ln_quant(site.x, site.gamma, site.beta, EPS, False, c1.perm, c1.cluster_off, c1.inv_s, c1.z, bits)
+    wq1, sW1, _, zW1 = o.quantize_weights(W1, c1.perm, c2.perm)
+    _, _, H = o.cluster_gemm_int(rc1, wq1, c1.cluster_off, c1.s, c1.z, sW1, zW1)
+    tol = tol_of(H)
+    mid, _ = oracle_codes(H, relu, c2, bits2)
+    lo, _ = oracle_codes(H - tol, relu, c2, bits2)
+    hi, _ = oracle_codes(H + tol, relu, c2, bits2)
+    ok = ~fr1
+    assert ((lo <= got) & (got <= hi))[ok].all()
+    assert (got == mid)[ok].mean() >= 0.995
+
+    # the fused stage is the two-kernel path with the bf16 tensor left out: identical codes
+    lin1 = rp.fold_linear(k1, torch.from_numpy(W1).cuda(), perm_out=k2.perm_dev)
+    h = rp.cluster_gemm(k1, lin1, codes1, rt1, M, dtype=torch.bfloat16)
+    ident = rp.identity_site(k2)
+    codes2u, _, rt2u = rp.ln_quant(ident, h, EPS, relu=relu)
+    torch.cuda.synchronize()
+    assert torch.equal(codes2, codes2u)
+    # the de-quantized row sum that the next product's zero-point term needs, from the codes written
+    n_i = np.diff(c2.cluster_off)
+    xs = np.stack([got[:, a:b].sum(axis=1) for a, b in zip(c2.cluster_off[:-1], c2.cluster_off[1:])], axis=1)
+    want_rt = (c2.s.astype(np.float64) * (xs - n_i * c2.z.astype(np.int64))).sum(axis=1)
+    assert np.allclose(rt2.cpu().numpy(), want_rt, rtol=2e-6, atol=1e-6 * np.abs(want_rt).max())
+    assert np.allclose(rt2.cpu().numpy(), rt2u.cpu().numpy(), rtol=2e-6, atol=1e-6 * np.abs(want_rt).max())
+
+    # and the next product reads them: fc2 on the fused codes = the oracle's fc2 on the same codes
+    lin2 = rp.fold_linear(k2, torch.from_numpy(W2).cuda())
+    y = rp.cluster_gemm(k2, lin2, codes2, rt2, M, dtype=torch.float32)
+    wq2, sW2, _, zW2 = o.quantize_weights(W2, c2.perm)
+    if (got == mid)[ok].all():                           # the oracle's own codes: nothing from the device enters
+        _, _, Y = o.cluster_gemm_int(mid, wq2, c2.cluster_off, c2.s, c2.z, sW2, zW2)
+        assert (np.abs(y.cpu().numpy().astype(np.float64) - Y)[ok] <= tol_of(Y)[ok]).all()
+
+
+def test_pad_rows_of_the_output_layout_are_zero(rp):
+    """fold_reorder with -1 entries in perm_out: weights 0, sW 1, zW 0 -> those outputs are 0,
+    and the other outputs are what the layer without pad rows gives."""
+    d, n_real, n_out, M, bits, g = 128, 24, 128, 40, 4, 4
+    site = w.make_site(5150, d, M, 2, 64)
+    gamma, beta = torch.from_numpy(site.gamma).cuda(), torch.from_numpy(site.beta).cuda()
+    k1 = rp.calibrate_site([dev_bf16(b) for b in site.cal], gamma, beta, EPS, False, g, bits, seed=5150)
+    W = torch.from_numpy(w.weight_matrix(5151, n_real, d)).cuda()
+    rows = np.full(n_out, -1, dtype=np.int32)
+    rows[3::5][:n_real] = np.arange(n_real, dtype=np.int32)
+    assert (rows >= 0).sum() == n_real
+    lin = rp.FoldedLinear(N=n_out,
+                          Wq=torch.empty(rp.rptq_weight_bytes(n_out, k1.k_padded), dtype=torch.uint8, device="cuda"),
+                          sW=torch.empty(n_out, dtype=torch.float32, device="cuda"),
+                          zW=torch.empty(n_out, dtype=torch.int32, device="cuda"),
+                          wsum=torch.empty((n_out, k1.g_eff), dtype=torch.int32, device="cuda"),
+                          colterm=torch.empty(n_out, dtype=torch.float32, device="cuda"))
+    rp.rptq_fold_reorder(None, None, k1.d, k1.perm_dev, k1.perm, k1.cluster_off, k1.s, k1.z, W, n_out, d,
+                         torch.from_numpy(rows).cuda(), k1.perm_pad, None, None, lin.Wq, lin.sW, lin.zW,
+                         lin.wsum, lin.colterm)
+    codes, _, rt = rp.ln_quant(k1, dev_bf16(site.x), EPS)
+    y = rp.cluster_gemm(k1, lin, codes, rt, M, dtype=torch.float32).cpu().numpy()
+    pad = rows < 0
+    assert (y[:, pad] == 0).all()
+    assert (lin.sW.cpu().numpy()[pad] == 1).all() and (lin.zW.cpu().numpy()[pad] == 0).all()
+    assert (lin.wsum.cpu().numpy()[pad] == 0).all() and (lin.colterm.cpu().numpy()[pad] == 0).all()
+    plain = rp.fold_linear(k1, W)
+    y0 = rp.cluster_gemm(k1, plain, codes, rt, M, dtype=torch.float32).cpu().numpy()
+    assert np.array_equal(y[:, ~pad], y0)
