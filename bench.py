@@ -38,10 +38,10 @@ def parse_args():
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: OPT-1.3b layer)")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/weight copies cycled through the steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--fuse-next-site", action="store_true",
-                    help="chained workloads: quantize for the next site in fc1's output stage "
-                         "(rptq_cluster_gemm_quant) instead of storing fc1's bf16 output and quantizing it "
-                         "with a second kernel")
+    ap.add_argument("--unfused", action="store_true",
+                    help="chained workloads: store fc1's bf16 output and quantize it with a second kernel "
+                         "(rptq_cluster_gemm + rptq_ln_quant) instead of quantizing for the next site in "
+                         "fc1's output stage (rptq_cluster_gemm_quant)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to scale profiler byte counters)")
     return ap.parse_args()
@@ -101,7 +101,7 @@ def main():
             cal = rp.calibrate_site(hcal, None, None, EPS, True, spec.g, bits, seed=seed)
             del hcal
             prev["row_perm_host"] = cal.perm
-            if not args.fuse_next_site:
+            if args.unfused:
                 prev["perm_out"][0] = cal.perm_dev      # fc1's rows leave in this site's cluster order
             else:
                 prev["next_site"] = cal                 # ... and padded like it: fc1's output stage quantizes

@@ -422,6 +422,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
               make_float4(facc[i][j][q * 4 + 0], facc[i][j][q * 4 + 1], facc[i][j][q * 4 + 2], facc[i][j][q * 4 + 3]);
         }
     __syncthreads();
+    double q_part[NPASS];                                   // quantizing stage: this thread's share of each row's de-quantized sum
     const bool vec_ok = (a.N % 8) == 0 && n + CW <= a.N;
     unsigned char* ybase = static_cast<unsigned char*>(a.y);
 #pragma unroll
@@ -472,10 +473,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
             *reinterpret_cast<uint32_t*>(qo.codes + t * qo.row_bytes + (n >> 1)) = ((D[0] << 4) | D[1]) ^ 0x88888888u;
           }
         }
-        // the row's share of this column tile: sum over the CPR lanes that hold the row
-#pragma unroll
-        for (int m = CPR / 2; m >= 1; m >>= 1) part += __shfl_xor(part, m, kWave);
-        if (cc == 0 && t < a.M) qo.rt_part[static_cast<int64_t>(lin / tiles_m) * a.M + t] = part;
+        q_part[pass] = part;
       } else if (t < a.M) {
         if (YF32) {
           if (vec_ok) {
@@ -503,15 +501,51 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
         }
       }
     }
+    if (QOUT) {
+      // Row sums of this column tile: each row's NPASS-th share sits in the CPR lanes that hold
+      // the row.  Halving exchange: at each of the first log2(NPASS) steps a lane hands half of
+      // its values to its partner and keeps the sums of the other half, so that it ends with
+      // one value; plain exchanges over the remaining lane bits finish the sum.  The total of
+      // pass p lands in the lanes whose upper log2(NPASS) bits of cc spell p.
+      static_assert((NPASS & (NPASS - 1)) == 0 && NPASS <= CPR, "row-sum exchange");
+      int have = NPASS, m = CPR / 2;
+#pragma unroll
+      for (; have > 1; have >>= 1, m >>= 1) {
+        const bool upper = (cc & m) != 0;
+#pragma unroll
+        for (int k = 0; k < NPASS / 2; ++k) {
+          if (k < have / 2) {
+            const double send = upper ? q_part[k] : q_part[k + have / 2];
+            const double keep = upper ? q_part[k + have / 2] : q_part[k];
+            q_part[k] = keep + __shfl_xor(send, m, kWave);
+          }
+        }
+      }
+      double total = q_part[0];
+#pragma unroll
+      for (; m >= 1; m >>= 1) total += __shfl_xor(total, m, kWave);
+      constexpr int LPP = CPR / NPASS;                      // lanes per pass
+      const int64_t t = m0 + (cc / LPP) * RPP + rr;
+      if ((cc % LPP) == 0 && t < a.M) qo.rt_part[static_cast<int64_t>(lin / tiles_m) * a.M + t] = total;
+    }
   }
 }
 
 // Sum over the column tiles, in tile order, of the row sums the quantizing output stage left.
-__global__ void __launch_bounds__(256) rowterm_reduce_kernel(const double* part, int tiles_n, int64_t M, float* rowterm) {
-  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+__global__ void __launch_bounds__(64) rowterm_reduce_kernel(const double* part, int tiles_n, int64_t M, float* rowterm) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 64 + threadIdx.x;
   if (t >= M) return;
+  // sixteen independent loads in flight, added in tile order (a thread per row has little else to hide latency with)
   double acc = 0.0;
-  for (int j = 0; j < tiles_n; ++j) acc += part[static_cast<int64_t>(j) * M + t];
+  int j = 0;
+  for (; j + 16 <= tiles_n; j += 16) {
+    double v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = part[static_cast<int64_t>(j + k) * M + t];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc += v[k];
+  }
+  for (; j < tiles_n; ++j) acc += part[static_cast<int64_t>(j) * M + t];
   rowterm[t] = static_cast<float>(acc);
 }
 
@@ -531,7 +565,7 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuant
   hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab, qo);
   RPTQ_HIP(hipGetLastError());
   if (OUT >= 2) {
-    hipLaunchKernelGGL(rowterm_reduce_kernel, dim3(static_cast<unsigned>((a.M + 255) / 256)), dim3(256), 0, st,
+    hipLaunchKernelGGL(rowterm_reduce_kernel, dim3(static_cast<unsigned>((a.M + 63) / 64)), dim3(64), 0, st,
                        qo.rt_part, b.tiles_n, a.M, q_rowterm);
     RPTQ_HIP(hipGetLastError());
   }
