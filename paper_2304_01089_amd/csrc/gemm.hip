@@ -62,6 +62,14 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* sA = smem;                               // [2][A_STAGE]
+  // behind the pipeline buffers / the output tile (they share the front of the LDS): the
+  // per-channel and per-row terms of the output stage, fetched in the prologue
+  constexpr int kStageBytes = PARTIALS ? 0 : BM * (BN + 4) * 4;
+  constexpr int kConstOff = (2 * A_STAGE > kStageBytes) ? 2 * A_STAGE : kStageBytes;
+  float* c_sw = reinterpret_cast<float*>(smem + kConstOff);   // [BN]
+  float* c_ct = c_sw + BN;                                     // [BN]
+  float* c_zw = c_ct + BN;                                     // [BN]
+  float* c_rt = c_zw + BN;                                     // [BM]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -199,6 +207,21 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   load_a(0, 0);
   load_w(0);
   load_a(min(1, last), 1);
+  // output-stage terms of this tile (thread i: channel n0 + i, token m0 + i; reads past the end
+  // of a vector return 0 and belong to outputs that are never stored)
+  float p_sw = 0.0f, p_ct = 0.0f, p_zw = 0.0f, p_rt = 0.0f;
+  if (!PARTIALS) {
+    const __amdgpu_buffer_rsrc_t sw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.sW), 0, a.N * 4, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t ct_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.colterm), 0, a.N * 4, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t zw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.zW), 0, a.N * 4, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(a.rowterm) + m0, 0, static_cast<int>(rows_here) * 4, kRsrcFlags);
+    const int ci = tid % BN, ri = tid % BM;
+    p_sw = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sw_rsrc, (n0 + ci) * 4, 0, 0));
+    p_ct = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ct_rsrc, (n0 + ci) * 4, 0, 0));
+    p_zw = static_cast<float>(static_cast<int32_t>(__builtin_amdgcn_raw_buffer_load_b32(zw_rsrc, (n0 + ci) * 4, 0, 0)));
+    p_rt = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rt_rsrc, ri * 4, 0, 0));
+  }
 #pragma unroll
   for (int u = 0; u < A_PER; ++u) {
     store_a_half(0, 0, u, 0);
@@ -207,6 +230,12 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   // every prologue load has landed before the loop starts: the loop's own waits then count
   // only the loads of the steady state (vmcnt(0); the other counters are left alone)
   __builtin_amdgcn_s_waitcnt(0x0F70);
+  if (!PARTIALS) {                                          // (threads beyond BN / BM repeat a valid entry)
+    c_sw[tid % BN] = p_sw;
+    c_ct[tid % BN] = p_ct;
+    c_zw[tid % BN] = p_zw;
+    c_rt[tid % BM] = p_rt;
+  }
   __syncthreads();
   load_a(min(2, last), 0);
 
@@ -354,35 +383,22 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     constexpr int NPASS = BM / RPP;
     static_assert(256 % CPR == 0 && BM % RPP == 0, "output tiling");
     float* tile = reinterpret_cast<float*>(smem);
-    // per-channel and per-row terms of this thread's share: requested first, so that their
-    // latency runs under the LDS transpose
+    // per-channel and per-row terms of this thread's share, from the copies the prologue left in
+    // LDS: the output stage issues no load, so it never waits behind the main loop's last ones
     const int cc = tid % CPR, rr = tid / CPR;
     const int n = n0 + cc * CW;
     float sw[CW], ct[CW], zw[CW], rt[NPASS];
-    {
-      // (buffer loads: 16 bytes at a time, reads past the end of a vector return 0 and belong to
-      // outputs that are never stored)
-      const __amdgpu_buffer_rsrc_t sw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.sW), 0, a.N * 4, kRsrcFlags);
-      const __amdgpu_buffer_rsrc_t ct_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.colterm), 0, a.N * 4, kRsrcFlags);
-      const __amdgpu_buffer_rsrc_t zw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.zW), 0, a.N * 4, kRsrcFlags);
-      const __amdgpu_buffer_rsrc_t rt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<float*>(a.rowterm) + m0, 0, static_cast<int>(rows_here) * 4, kRsrcFlags);
 #pragma unroll
-      for (int e4 = 0; e4 < CW / 4; ++e4) {
-        const u4v s4 = __builtin_amdgcn_raw_buffer_load_b128(sw_rsrc, (n + e4 * 4) * 4, 0, 0);
-        const u4v c4 = __builtin_amdgcn_raw_buffer_load_b128(ct_rsrc, (n + e4 * 4) * 4, 0, 0);
-        const u4v z4 = __builtin_amdgcn_raw_buffer_load_b128(zw_rsrc, (n + e4 * 4) * 4, 0, 0);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          sw[e4 * 4 + k] = __uint_as_float(s4[k]);
-          ct[e4 * 4 + k] = __uint_as_float(c4[k]);
-          zw[e4 * 4 + k] = static_cast<float>(static_cast<int32_t>(z4[k]));
-        }
-      }
-#pragma unroll
-      for (int pass = 0; pass < NPASS; ++pass)
-        rt[pass] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rt_rsrc, (pass * RPP + rr) * 4, 0, 0));
+    for (int e4 = 0; e4 < CW / 4; ++e4) {
+      const float4 s4 = *reinterpret_cast<const float4*>(c_sw + cc * CW + e4 * 4);
+      const float4 c4 = *reinterpret_cast<const float4*>(c_ct + cc * CW + e4 * 4);
+      const float4 z4 = *reinterpret_cast<const float4*>(c_zw + cc * CW + e4 * 4);
+      sw[e4 * 4 + 0] = s4.x; sw[e4 * 4 + 1] = s4.y; sw[e4 * 4 + 2] = s4.z; sw[e4 * 4 + 3] = s4.w;
+      ct[e4 * 4 + 0] = c4.x; ct[e4 * 4 + 1] = c4.y; ct[e4 * 4 + 2] = c4.z; ct[e4 * 4 + 3] = c4.w;
+      zw[e4 * 4 + 0] = z4.x; zw[e4 * 4 + 1] = z4.y; zw[e4 * 4 + 2] = z4.z; zw[e4 * 4 + 3] = z4.w;
     }
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) rt[pass] = c_rt[pass * RPP + rr];
     // quantizing output stage: this thread's eight columns are one unit (8 codes) of the next
     // site's layout and lie in one cluster; its constants, and which of the eight are padding
     constexpr int QB = QOUT ? OUT : 8;                      // bits of the codes written
@@ -555,7 +571,8 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuant
   constexpr int BM = WGM * WM * 32, BN = WGN * WN * 32;
   constexpr size_t pipe = 2 * kStepSlices * (2 * BM * 16 + kSlicePad);
   constexpr size_t stage = PARTIALS ? 0 : static_cast<size_t>(BM) * (BN + 4) * 4;   // fp32 output tile of the workgroup
-  constexpr size_t shmem = pipe > stage ? pipe : stage;
+  constexpr size_t terms = PARTIALS ? 0 : static_cast<size_t>(3 * BN + BM) * 4;     // output-stage vectors of the tile
+  constexpr size_t shmem = (pipe > stage ? pipe : stage) + terms;
   auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, OUT>;
   if (shmem > 64 * 1024) RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
   GemmArgs b = a;
