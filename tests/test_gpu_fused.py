@@ -141,3 +141,63 @@ def test_pad_rows_of_the_output_layout_are_zero(rp):
     plain = rp.fold_linear(k1, W)
     y0 = rp.cluster_gemm(k1, plain, codes, rt, M, dtype=torch.float32).cpu().numpy()
     assert np.array_equal(y[:, ~pad], y0)
+
+
+def test_config2_full_size_sampled(rp):
+    """BASELINE configs[2] at full size, as bench.py launches it (fc1's output stage quantizes for
+    fc2's site): sampled tokens against the oracle's bracket, every token against the two-kernel
+    path.  Calibration uses 4 batches (the hidden calibration tensor is computed on the host)."""
+    cfg = w.CONFIGS[2]
+    s1, s2 = cfg.sites
+    M, bits = cfg.M, cfg.bits
+    dff = s1.gemms[0][1]
+    seed1, seed2 = w.site_seed(2, 0), w.site_seed(2, 1)
+    rows, n_cal = 512, 4
+    site = w.make_site(seed1, s1.d, rows, n_cal)
+    W1 = w.weight_rows(seed1 + 500, dff, s1.d, np.arange(dff))
+    c1 = o.calibrate(site.cal, site.gamma, site.beta, EPS, False, s1.g, bits, seed=seed1)
+
+    def fp_hidden(x):                                   # unquantized model, float32 on the host: an input to both sides
+        y, _ = o.layernorm_f32(x, site.gamma, site.beta, EPS)
+        return w.round_to_bf16(y @ W1.T)
+    hcal = [fp_hidden(b) for b in site.cal]
+    c2 = o.calibrate(hcal, None, None, EPS, True, s2.g, bits, seed=seed2)
+
+    gamma, beta = torch.from_numpy(site.gamma).cuda(), torch.from_numpy(site.beta).cuda()
+    k1 = rp.calibrate_site([dev_bf16(b) for b in site.cal], gamma, beta, EPS, False, s1.g, bits, seed=seed1)
+    k2 = rp.calibrate_site([dev_bf16(h) for h in hcal], None, None, EPS, True, s2.g, bits, seed=seed2)
+    assert np.array_equal(k1.perm, c1.perm) and np.array_equal(k2.perm, c2.perm)
+    assert np.array_equal(k2.z, c2.z) and np.array_equal(k2.s, c2.s)
+
+    W1d = torch.from_numpy(W1).cuda()
+    lin1q = rp.fold_linear(k1, W1d, next_site=k2)
+    x = dev_bf16(site.x).repeat((M + rows - 1) // rows, 1)[:M].contiguous()
+    codes1, _, rt1 = rp.ln_quant(k1, x, EPS)
+    codes2, rt2 = rp.cluster_gemm_quant(k1, lin1q, codes1, rt1, M, k2, relu=True)
+    got_all = torch.empty((M, dff), dtype=torch.int8, device="cuda")
+    rp.rptq_unpack_codes(codes2, M, k2.cluster_off, bits, got_all)
+
+    rng = np.random.default_rng(2)
+    ts = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 14)]))
+    got = got_all[torch.from_numpy(ts).cuda()].cpu().numpy().astype(np.int64)
+    rc1, _, fr1 = o.ln_quant(site.x[ts % rows], site.gamma, site.beta, EPS, False, c1.perm, c1.cluster_off,
+                             c1.inv_s, c1.z, bits)
+    wq1, sW1, _, zW1 = o.quantize_weights(W1, c1.perm, c2.perm)
+    _, _, H = o.cluster_gemm_int(rc1, wq1, c1.cluster_off, c1.s, c1.z, sW1, zW1)
+    tol = tol_of(H)
+    mid, _ = oracle_codes(H, True, c2, bits)
+    lo, _ = oracle_codes(H - tol, True, c2, bits)
+    hi, _ = oracle_codes(H + tol, True, c2, bits)
+    ok = ~fr1
+    assert ok.sum() >= len(ts) - 2
+    assert ((lo <= got) & (got <= hi))[ok].all()
+    assert (got == mid)[ok].mean() >= 0.995
+
+    # every token: identical to the product stored as bf16 and quantized by the second kernel
+    lin1 = rp.fold_linear(k1, W1d, perm_out=k2.perm_dev)
+    h = rp.cluster_gemm(k1, lin1, codes1, rt1, M, dtype=torch.bfloat16)
+    codes2u, _, rt2u = rp.ln_quant(rp.identity_site(k2), h, EPS, relu=True)
+    torch.cuda.synchronize()
+    assert torch.equal(codes2, codes2u)
+    a, b = rt2.cpu().numpy(), rt2u.cpu().numpy()
+    assert np.allclose(a, b, rtol=2e-6, atol=1e-6 * np.abs(b).max())
