@@ -144,6 +144,32 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     return;
   }
 
+  // ---- this thread's 16-byte chunks of an input row ---------------------------------------
+  int ch_idx[NCH];                   // chunk index, clamped for surplus lanes
+  int ch_lds[NCH];                   // LDS byte offset inside a row buffer (surplus lanes: the spare slot)
+  bool ch_ok[NCH];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int idx = tid + c * TU;
+    ch_ok[c] = idx < a.chunks;
+    ch_idx[c] = ch_ok[c] ? idx : a.chunks - 1;
+    ch_lds[c] = ch_ok[c] ? idx * 16 : a.d * 2;
+  }
+  constexpr bool kTwoAhead = NCH <= 2;               // registers permitting, the first two rows are requested at once
+  uint4 nxt[NCH], nx1[kTwoAhead ? NCH : 1];
+  auto fetch_row = [&](int k, uint4* dst) {          // k-th row of this workgroup; past the end: a valid row again
+    int64_t row = row0 + k * stride;
+    if (row >= a.M) row = a.M - 1;
+    const uint4* p = a.x + row * a.chunks;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) dst[c] = p[ch_idx[c]];
+  };
+  auto load_row = [&](int k) { fetch_row(k, nxt); };
+  // the first rows are requested before anything else, so that their latency runs under the
+  // loads of the per-thread constants below instead of after them
+  fetch_row(0, nxt);
+  if (kTwoAhead) fetch_row(1, nx1);
+
   // ---- unit waves: per-thread constants, loaded once -----------------------------------------
   uint32_t src[NUNIT][UC];           // LDS byte offsets of the source channels inside a row buffer
   float gam[LN ? NUNIT : 1][LN ? UC : 1];
@@ -210,25 +236,6 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     usum_fix[n] = UC * kQMin - n_real * qt.z[ci];
   }
 
-  // ---- this thread's 16-byte chunks of an input row ---------------------------------------
-  int ch_idx[NCH];                   // chunk index, clamped for surplus lanes
-  int ch_lds[NCH];                   // LDS byte offset inside a row buffer (surplus lanes: the spare slot)
-  bool ch_ok[NCH];
-#pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    const int idx = tid + c * TU;
-    ch_ok[c] = idx < a.chunks;
-    ch_idx[c] = ch_ok[c] ? idx : a.chunks - 1;
-    ch_lds[c] = ch_ok[c] ? idx * 16 : a.d * 2;
-  }
-  uint4 nxt[NCH];
-  auto load_row = [&](int k) {                       // k-th row of this workgroup; past the end: a valid row again
-    int64_t row = row0 + k * stride;
-    if (row >= a.M) row = a.M - 1;
-    const uint4* p = a.x + row * a.chunks;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) nxt[c] = p[ch_idx[c]];
-  };
   // registers -> row buffer, exact fp64 sums of this thread's elements -> partials
   auto stage_row = [&](unsigned char* rowbuf, int pb) {
     double s1 = 0.0, s2 = 0.0;
@@ -257,9 +264,13 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
 
   // ---- pipelined row loop --------------------------------------------------------------------
   int b_cur = 0, b_next = lds.rowbuf_bytes, b_spare = (a.ring == 3) ? 2 * lds.rowbuf_bytes : 0;
-  load_row(0);
   stage_row(smem + b_cur, 0);
-  load_row(1);
+  if (kTwoAhead) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) nxt[c] = nx1[c];
+  } else {
+    load_row(1);
+  }
   __syncthreads();                                             // row 0 staged
 
   for (int i = 0; i < n_rows; ++i) {
