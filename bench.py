@@ -42,6 +42,10 @@ def parse_args():
                     help="chained workloads: store fc1's bf16 output and quantize it with a second kernel "
                          "(rptq_cluster_gemm + rptq_ln_quant) instead of quantizing for the next site in "
                          "fc1's output stage (rptq_cluster_gemm_quant)")
+    ap.add_argument("--library-int8-probe", action="store_true",
+                    help="also time the ROCm library's plain int8 GEMM (torch._int_mm: int8 x int8 -> int32, no "
+                         "unpacking, no per-cluster scales, no output arithmetic) at the workload's GEMM shapes: "
+                         "context for the int8 fractions, not part of the path")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to scale profiler byte counters)")
     return ap.parse_args()
@@ -296,6 +300,35 @@ def main():
                    sample="%d of %d tokens, all sites and GEMMs of the workload, numpy float64/int64 oracle "
                           "(offline weight quantization excluded)" % (rows, M), seconds=round(online, 3))
 
+    # ---- context: the vendor library's plain int8 GEMM at the same shapes ---------------------------
+    probe = None
+    if args.library_int8_probe:
+        probe = {}
+        for s in sites:
+            for lin in s["lins"]:
+                K, N = s["spec"].d, lin["N"]
+                a8 = torch.randint(-8, 8, (max(M, 32), K), dtype=torch.int8, device="cuda")
+                b8 = torch.randint(-8, 8, (N, K), dtype=torch.int8, device="cuda").t()     # weights stored [N, K]
+                t_ramp = time.time()
+                while time.time() - t_ramp < 1.0:
+                    for _ in range(20):
+                        torch._int_mm(a8, b8)
+                    torch.cuda.synchronize()
+                reps = []
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(20):
+                        torch._int_mm(a8, b8)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    reps.append(e0.elapsed_time(e1) / 20)
+                ms = float(np.median(reps))
+                tops = 2.0 * a8.shape[0] * N * K / (ms * 1e-3) * 1e-12
+                probe["%s %dx%dx%d" % (lin["name"], a8.shape[0], N, K)] = dict(
+                    ms=round(ms, 5), achieved=round(tops, 1), unit="TOP/s", frac=round(tops / PEAK_INT8_TOPS, 4))
+                del a8, b8
+
     out = {
         "metric": "tokens/s for LN+quant+cluster-GEMM per layer; % HBM GB/s or int8 MFMA peak",
         "value": round(tokens_per_s, 1),
@@ -319,6 +352,8 @@ def main():
         "stages": stages,
         "cpu_baseline": cpu,
     }
+    if probe is not None:
+        out["library_int8_gemm"] = probe
     print(json.dumps(out))
 
 
