@@ -405,10 +405,8 @@ template <int BITS, int NUNIT, int NCH, bool LN>
 static int32_t launch_kernel(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, int threads,
                              int64_t want_grid, int lds_per_cu, size_t shmem, hipStream_t st) {
   auto kern = ln_quant_kernel<BITS, NUNIT, NCH, LN>;
-  if (shmem > 64 * 1024) {
-    RPTQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 static_cast<int>(shmem)));
-  }
+  static int lds_granted[kMaxDevices] = {0};
+  if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, lds_granted)) return st_lds;
   // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round.
   // (the last answer is kept: a serving loop asks for the same launch shape again and again)
   static int cached_threads = -1, cached_per_cu = 0;

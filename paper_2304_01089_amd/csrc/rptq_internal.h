@@ -46,6 +46,22 @@ int32_t hip_fail(hipError_t e);
     if (e_ != hipSuccess) return ::rptq::hip_fail(e_);   \
   } while (0)
 
+// Raises a kernel's dynamic-LDS limit when a launch needs more than the default 64 KiB.  The
+// driver call is made once per device and size (granted[] belongs to one kernel: a static
+// array of kMaxDevices zeros in its launcher), so that repeated launches, and launches under
+// stream capture, make no driver call at all.
+constexpr int kMaxDevices = 64;
+inline int32_t ensure_dynamic_lds(const void* kern, size_t bytes, int* granted) {
+  if (bytes <= 64 * 1024) return RPTQ_OK;
+  int dev = 0;
+  RPTQ_HIP(hipGetDevice(&dev));
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  if (tracked && granted[dev] >= static_cast<int>(bytes)) return RPTQ_OK;
+  RPTQ_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)));
+  if (tracked) granted[dev] = static_cast<int>(bytes);
+  return RPTQ_OK;
+}
+
 // Host clustering (host.cpp), exposed through rptq_cluster_channels.
 int32_t cluster_channels(const float* ch_min, const float* ch_max, int32_t d, int32_t g, int32_t bits,
                          uint64_t seed, int32_t max_iter, int32_t* assign, int32_t* perm,
