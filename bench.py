@@ -43,9 +43,9 @@ def parse_args():
                          "(rptq_cluster_gemm + rptq_ln_quant) instead of quantizing for the next site in "
                          "fc1's output stage (rptq_cluster_gemm_quant)")
     ap.add_argument("--library-int8-probe", action="store_true",
-                    help="also time the ROCm library's plain int8 GEMM (torch._int_mm: int8 x int8 -> int32, no "
-                         "unpacking, no per-cluster scales, no output arithmetic) at the workload's GEMM shapes: "
-                         "context for the int8 fractions, not part of the path")
+                    help="also time the ROCm library's plain GEMMs at the workload's GEMM shapes: int8 x int8 -> int32 "
+                         "(torch._int_mm: no unpacking, no per-cluster scales, no output arithmetic) and bf16 (torch.mm: "
+                         "what App. A.4's first method would run after de-quantizing); context, not part of the path")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to scale profiler byte counters)")
     return ap.parse_args()
@@ -325,9 +325,25 @@ def main():
                     reps.append(e0.elapsed_time(e1) / 20)
                 ms = float(np.median(reps))
                 tops = 2.0 * a8.shape[0] * N * K / (ms * 1e-3) * 1e-12
+                a16 = torch.randn((a8.shape[0], K), dtype=torch.bfloat16, device="cuda")
+                b16 = torch.randn((N, K), dtype=torch.bfloat16, device="cuda").t()
+                for _ in range(40):
+                    torch.mm(a16, b16)
+                torch.cuda.synchronize()
+                reps16 = []
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(20):
+                        torch.mm(a16, b16)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    reps16.append(e0.elapsed_time(e1) / 20)
+                ms16 = float(np.median(reps16))
                 probe["%s %dx%dx%d" % (lin["name"], a8.shape[0], N, K)] = dict(
-                    ms=round(ms, 5), achieved=round(tops, 1), unit="TOP/s", frac=round(tops / PEAK_INT8_TOPS, 4))
-                del a8, b8
+                    ms=round(ms, 5), achieved=round(tops, 1), unit="TOP/s", frac=round(tops / PEAK_INT8_TOPS, 4),
+                    bf16_ms=round(ms16, 5))
+                del a8, b8, a16, b16
 
     out = {
         "metric": "tokens/s for LN+quant+cluster-GEMM per layer; % HBM GB/s or int8 MFMA peak",
