@@ -56,8 +56,10 @@ struct GemmQuantOut {
 };
 
 constexpr int kStepSlices = 8;            // slices per K step (256 codes): one barrier per step
-constexpr int kSlicePad = 64;             // bytes added to a slice's LDS stride: 16 banks, so the four
-                                          // slices a 16-lane write group touches fall in distinct banks
+constexpr int kSlicePad = 16;             // bytes added to a slice's LDS stride.  The staging stores of 8 consecutive
+                                          // lanes go to the 8 slices of one row: with a stride of 2^n + 16 bytes they
+                                          // fall into distinct 16-byte bank groups (a stride of 2^n + 64 put them into
+                                          // two groups: 2-4 % slower on every shape)
 
 template <int BITS>
 struct ActFmt {
