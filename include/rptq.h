@@ -204,8 +204,7 @@ int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
  *
  *  first twelve arguments: as rptq_cluster_gemm; N must equal the next site's K_p
  *  relu       != 0: max(h,0) before quantizing
- *  next_*     host: the next site's cluster_off [next_g+1], s, inv_s, z [next_g]; next_bits in {4,8}
- *             (RPTQ_ERR_BITS otherwise)
+ *  next_*     host: the next site's cluster_off [next_g+1], s, inv_s, z [next_g]; next_bits in {3,4,8}
  *  next_codes device out, rptq_codes_bytes(M, N, next_bits)
  *  next_rowterm device fp32 [M] out: as rptq_ln_quant's rowterm, for the next product
  *  workspace  device, rptq_cluster_gemm_quant_workspace_bytes(M, N) (RPTQ_ERR_WORKSPACE if

@@ -178,7 +178,7 @@ int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bit
   if (!codes_packed || !Wq_packed || !sX || !sW || !zW || !colterm || !rowterm) return RPTQ_ERR_NULL;
   if (!next_s || !next_inv_s || !next_z || !next_codes || !next_rowterm || !workspace) return RPTQ_ERR_NULL;
   if (int32_t st = check_bits(bits)) return st;
-  if (next_bits != 4 && next_bits != 8) return RPTQ_ERR_BITS;
+  if (int32_t st = check_bits(next_bits)) return st;
   ClusterGeom geom, next;
   if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
   if (int32_t st = check_clusters(next_cluster_off, next_g, &next)) return st;

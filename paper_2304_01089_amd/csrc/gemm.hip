@@ -44,7 +44,7 @@ __device__ __forceinline__ void unpack3(uint32_t x0, uint32_t x1, uint32_t x2, u
   hi->w = ((x1 << 6) & 0xc0c0c0c0u) | ((x2 << 4) & 0x20202020u);
 }
 
-// OUT: what the output stage writes - kOutBf16 / kOutF32: Y; 4 or 8: the next site's packed
+// OUT: what the output stage writes - kOutBf16 / kOutF32: Y; 3, 4 or 8: the next site's packed
 // codes of that many bits (ReLU optional) and the partial row sums its product needs.
 constexpr int kOutBf16 = 0, kOutF32 = 1;
 template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT>
@@ -479,7 +479,22 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
         const uint32_t usum = __builtin_amdgcn_sad_u8(D[1], 0u, __builtin_amdgcn_sad_u8(D[0], 0u, 0u));
         const bool live = t < a.M && n < a.N;
         double part = live ? q_s * static_cast<double>(static_cast<int32_t>(usum) + q_fix) : 0.0;
-        if (live) {
+        if (QB == 3) {
+          // 32 codes in 12 bytes (x0, x1, x2), the four threads of a lane quad hold codes 8k..8k+7:
+          // k = 0, 1, 2 own bits 7..2 of x_k; the thread with k = 3 (codes 24..31) supplies the low
+          // two bits of x0 and x1 (upper two bits of its codes) and bits 0, 1 of x2 (their low bits)
+          const int k = cc & 3;
+          const uint32_t main3 = ((D[0] << 5) | (D[1] << 2)) ^ 0x90909090u;
+          const uint32_t p0 = ((D[0] >> 1) & 0x03030303u) ^ 0x02020202u;
+          const uint32_t p1 = ((D[1] >> 1) & 0x03030303u) ^ 0x02020202u;
+          const uint32_t p2 = (D[0] & 0x01010101u) | ((D[1] & 0x01010101u) << 1);
+          const uint32_t b0 = static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(p0), 0xFF, 0xF, 0xF, true));
+          const uint32_t b1 = static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(p1), 0xFF, 0xF, 0xF, true));
+          const uint32_t b2 = static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(p2), 0xFF, 0xF, 0xF, true));
+          const uint32_t word = main3 | (k == 0 ? b0 : (k == 1 ? b1 : b2));
+          if (live && k < 3)
+            *reinterpret_cast<uint32_t*>(qo.codes + t * qo.row_bytes + (n >> 5) * 12 + k * 4) = word;
+        } else if (live) {
           if (QB == 8) {
             uint2 o;
             o.x = D[0] ^ 0x80808080u;
@@ -598,7 +613,7 @@ static int32_t launch_shape(const GemmArgs& a, const GemmTab& tab, const GemmQua
   return launch_cfg<BITS, 1, 4, 2, 2, PARTIALS, OUT>(a, tab, qo, q_rowterm, st);
 }
 
-// out_mode: -1 partial sums, kOutBf16, kOutF32, or the next site's code bits (4, 8)
+// out_mode: -1 partial sums, kOutBf16, kOutF32, or the next site's code bits (3, 4, 8)
 template <int BITS>
 static int32_t launch_bits(const GemmArgs& a, const GemmTab& tab, int out_mode, const GemmQuantOut& qo, float* q_rowterm,
                            hipStream_t st) {
@@ -606,6 +621,7 @@ static int32_t launch_bits(const GemmArgs& a, const GemmTab& tab, int out_mode, 
     case -1: return launch_shape<BITS, true, kOutF32>(a, tab, qo, q_rowterm, st);
     case kOutF32: return launch_shape<BITS, false, kOutF32>(a, tab, qo, q_rowterm, st);
     case kOutBf16: return launch_shape<BITS, false, kOutBf16>(a, tab, qo, q_rowterm, st);
+    case 3: return launch_shape<BITS, false, 3>(a, tab, qo, q_rowterm, st);
     case 4: return launch_shape<BITS, false, 4>(a, tab, qo, q_rowterm, st);
     case 8: return launch_shape<BITS, false, 8>(a, tab, qo, q_rowterm, st);
   }

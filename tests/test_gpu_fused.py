@@ -46,6 +46,8 @@ def oracle_codes(H, relu, c2, bits):
     ("a4_to_a8", 256, 1000, 70, 4, 8, 8, 5, True),        # next site at 8 bits, odd cluster count
     ("a8_to_a4_norelu", 128, 520, 64, 8, 4, 4, 8, False),
     ("a3_to_a4", 256, 768, 130, 3, 4, 8, 8, True),
+    ("a4_to_a3", 256, 1024, 150, 4, 3, 8, 8, True),
+    ("a3_to_a3_few_rows", 128, 520, 9, 3, 3, 4, 6, False),
     ("few_rows", 256, 1024, 20, 4, 4, 8, 8, True),        # the weight-streaming launch shape
     ("one_row", 128, 256, 1, 4, 4, 4, 4, True),
 ])

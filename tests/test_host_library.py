@@ -76,12 +76,12 @@ def test_validation_happens_before_any_device_work(lib):
     assert lib.rptq_ln_quant(dummy, 4, 16384, dummy, dummy, 1e-5, 0, dummy, wide, 1, one, one, zero, 4, dummy, None, None, None) == -2
     assert lib.rptq_cluster_gemm(dummy, 4, 4, dummy, 8, off, 1, one, dummy, dummy, dummy, None, dummy, 1, None) == -1
     assert lib.rptq_cluster_gemm(dummy, 4, 4, dummy, 0, off, 1, one, dummy, dummy, dummy, dummy, dummy, 1, None) == -2
-    # the quantizing output stage: 3-bit codes are not written, the product's width must be the
+    # the quantizing output stage: code widths as everywhere, the product's width must be the
     # next site's padded width, the workspace must be large enough
     off256 = (i32 * 2)(0, 256)
     gq = lambda N, nb, ws: lib.rptq_cluster_gemm_quant(dummy, 4, 4, dummy, N, off, 1, one, dummy, dummy, dummy, dummy, 1,
                                                       off256, 1, one, one, zero, nb, dummy, dummy, dummy, ws, None)
-    assert gq(256, 3, 1 << 20) == -3
+    assert gq(256, 5, 1 << 20) == -3
     assert gq(512, 4, 1 << 20) == -2
     assert gq(256, 4, 8) == -7
     assert rp.rptq_cluster_gemm_quant_workspace_bytes(100, 256) == 2 * 100 * 8
