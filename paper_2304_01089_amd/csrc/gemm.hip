@@ -204,6 +204,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   // always issued lets the compiler count outstanding loads exactly, and the surplus data of
   // the tail is never used)
   const int last = steps - 1;
+  __builtin_amdgcn_s_setprio(2);
   load_a(0, 0);
   load_w(0);
   load_a(min(1, last), 1);
@@ -335,6 +336,9 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
               }
             }
         } else {
+          // (while this wave works through the 2 x 16 x WM x WN instructions of the rescale it feeds
+          // the matrix pipe nothing: the other wave of the SIMD gets the issue slots first)
+          __builtin_amdgcn_s_setprio(0);
 #pragma unroll
           for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -342,6 +346,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 #pragma unroll
               for (int r = 0; r < 16; ++r)
                 facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
+          __builtin_amdgcn_s_setprio(2);
         }
         ++ci;
         next_end = __builtin_amdgcn_readlane(tab_end, ci & 63);
@@ -366,6 +371,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     k_step(step + 1, std::integral_constant<int, 1>());
   }
   if (step < steps) k_step(step, std::integral_constant<int, 0>());
+  __builtin_amdgcn_s_setprio(0);                             // the output stage yields to a co-resident main loop
 
   // ---- zero-point terms, output scale, store ----------------------------------------------------
   // D[n][t]: a lane holds one token (lane & 31) and, per register quad, four consecutive output
