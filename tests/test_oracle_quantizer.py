@@ -95,3 +95,35 @@ def test_saturation_far_outside_range():
     s, inv, z = o.minmax_params(np.float32(-1), np.float32(1), 3)
     q = o.quantize(np.array([-3e38, -1e9, 1e9, 3e38], dtype=np.float32), inv, z, 3)
     assert q.tolist() == [-4, -4, 3, 3]
+
+
+@pytest.mark.parametrize("k,relu", [(3, True), (4, True), (4, False), (8, True)])
+def test_bf16_rounding_then_quantizer_is_monotone(k, relu):
+    """The parity test of the product that quantizes for the next site brackets a code between the
+    oracle's codes of H - tol and H + tol.  That is only valid because rounding to bf16 (nearest
+    even), ReLU and Eq. 1 with the reciprocal multiply are each non-decreasing: checked here on
+    sorted inputs that include ties of both roundings, per cluster."""
+    import workloads as w
+    rng = np.random.default_rng(31 + k)
+    g, per = 5, 4000
+    s = np.exp(rng.normal(size=g)).astype(np.float32)
+    inv_s = (1.0 / s.astype(np.float64)).astype(np.float32)
+    z = rng.integers(-9, 10, size=g).astype(np.int32)
+    off = np.arange(g + 1, dtype=np.int32) * per
+    cols = []
+    for i in range(g):
+        qmax = 2 ** (k - 1)
+        x = rng.uniform(-1.5 * qmax, 1.5 * qmax, size=per - 200) * s[i]
+        ties = (np.arange(-100, 100) + 0.5) * s[i]                      # Eq. 1's rounding ties
+        cols.append(np.sort(np.concatenate([x, ties])).astype(np.float64))
+    H = np.concatenate(cols)[None, :]                                   # one row, clusters side by side
+    h = w.round_to_bf16(H.astype(np.float32))
+    codes, _, _ = o.ln_quant(h, None, None, 1e-5, relu, None, off, inv_s, z, k)
+    codes = codes[0].astype(np.int64)
+    for i in range(g):
+        seg = codes[off[i]:off[i + 1]]
+        assert (np.diff(seg) >= 0).all()
+        assert seg.min() >= -(2 ** (k - 1)) and seg.max() <= 2 ** (k - 1) - 1
+    hb = h[0].astype(np.float64)
+    for i in range(g):
+        assert (np.diff(hb[off[i]:off[i + 1]]) >= 0).all()
