@@ -38,11 +38,13 @@
  *    as App. A.4 says such values must be cast to a supported width).
  *
  * Packed weights: N_p = N rounded up to 256 rows, in blocks of 32 rows x 128 columns of K_p;
- *    block (rb, kb) starts at byte ((rb * K_p/128) + kb) * 2048 and holds 64 slots of 32 bytes;
- *    slot h*32 + r (h = 0,1) carries row rb*32+r; bytes 8s..8s+7 of the slot (s = 0..3) are
- *    columns kb*128 + s*32 + h*16 .. +15 as two 4-bit dwords in the 4-bit code format above.
- *    (One MFMA lane's operand bytes for four consecutive K slices are 32 contiguous bytes, a
- *    wave's are 2 KiB contiguous: weights stream from HBM straight into operand registers.)
+ *    block (rb, kb) starts at byte ((rb * K_p/128) + kb) * 2048 and holds two halves of 1 KiB
+ *    (K slices 0,1 and 2,3 of the block), each of 64 slots of 16 bytes; slot h*32 + r (h = 0,1)
+ *    carries row rb*32+r; bytes 8e..8e+7 of the slot (e = 0,1) are columns
+ *    kb*128 + (2*half + e)*32 + h*16 .. +15 as two 4-bit dwords in the 4-bit code format above.
+ *    (One MFMA lane's operand bytes for two consecutive K slices are 16 contiguous bytes, a
+ *    wave's are 1 KiB contiguous - eight whole cache lines per load: weights stream from HBM
+ *    straight into operand registers.)
  */
 #ifndef RPTQ_H
 #define RPTQ_H

@@ -32,7 +32,9 @@ __global__ void fold_ln_kernel(const float* gamma, const float* beta, const int3
 __device__ __host__ __forceinline__ size_t weight_dword_offset(int o, int u, int k_padded) {
   const int rb = o >> 5, r = o & 31;
   const int kb = u >> 4, s = (u >> 2) & 3, k8 = u & 3, h = k8 >> 1, v = k8 & 1;
-  return ((static_cast<size_t>(rb) * (k_padded / kWBlockCols) + kb) * 64 + h * 32 + r) * 32 + s * 8 + v * 4;
+  // block [rb][kb] of 2 KiB = two halves of 1 KiB (slices 0,1 | 2,3), each: 64 lanes x 16 bytes
+  return ((static_cast<size_t>(rb) * (k_padded / kWBlockCols) + kb) * 2 + (s >> 1)) * 1024 +
+         static_cast<size_t>(h * 32 + r) * 16 + (s & 1) * 8 + v * 4;
 }
 
 struct FoldArgs {

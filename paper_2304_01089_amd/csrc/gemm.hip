@@ -108,7 +108,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   }
   const int wblocks = a.slices / (kWBlockCols / kGroup);   // packed weight blocks per 32-row band
 #pragma unroll
-  for (int j = 0; j < WN; ++j) w_off[j] = ((wn * WN + j) * wblocks * 64 + lane) * 32;
+  for (int j = 0; j < WN; ++j) w_off[j] = (wn * WN + j) * wblocks * 2048 + lane * 16;
   const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(a.codes) + m0 * a.row_bytes, 0, static_cast<int>(rows_here) * a.row_bytes, kRsrcFlags);
   const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -135,8 +135,9 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   };
   // one slice pair (32 bytes per lane) of weight block j
   auto load_w_pair = [&](int step, int j, int pi) {
-    const u4v r = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_off[j] + (pi & 1) * 16,
-                                                        (step * (kStepSlices / 4) + (pi >> 1)) * 2048, 0);
+    // (a wave's load of a slice pair is 1 KiB contiguous: eight whole cache lines)
+    const u4v r = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_off[j],
+                                                        (step * (kStepSlices / 4) + (pi >> 1)) * 2048 + (pi & 1) * 1024, 0);
     wreg[j][pi] = make_uint4(r[0], r[1], r[2], r[3]);
   };
   auto load_w = [&](int step) {

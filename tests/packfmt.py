@@ -98,17 +98,17 @@ def pack_weights(wq, cluster_off):
     n_p = (N + N_ALIGN - 1) // N_ALIGN * N_ALIGN
     full = np.zeros((n_p, k_p), dtype=np.int64)
     full[:N] = p
-    # [rb, r, kb, s, h, v, 8 codes] -> [rb, kb, h, r, s, v, 4 bytes]
-    blk = full.reshape(n_p // 32, 32, k_p // 128, 4, 2, 2, 8)
-    by = _pack4_groups(blk)                                  # [rb, r, kb, s, h, v, 4]
-    by = by.transpose(0, 2, 4, 1, 3, 5, 6)                   # [rb, kb, h, r, s, v, 4]
+    # [rb, r, kb, sp, s2, h, v, 8 codes] -> [rb, kb, sp, h, r, s2, v, 4 bytes]   (slice s = 2 sp + s2)
+    blk = full.reshape(n_p // 32, 32, k_p // 128, 2, 2, 2, 2, 8)
+    by = _pack4_groups(blk)                                  # [rb, r, kb, sp, s2, h, v, 4]
+    by = by.transpose(0, 2, 3, 5, 1, 4, 6, 7)                # [rb, kb, sp, h, r, s2, v, 4]
     return np.ascontiguousarray(by).reshape(-1)
 
 
 def unpack_weights(packed, N, cluster_off):
     pad_off, k_p = padded_layout(cluster_off)
     n_p = (N + N_ALIGN - 1) // N_ALIGN * N_ALIGN
-    by = np.asarray(packed, dtype=np.uint8).reshape(n_p // 32, k_p // 128, 2, 32, 4, 2, 4).astype(np.int64)
-    codes = np.concatenate([_sext(by >> 4, 4), _sext(by & 15, 4)], axis=6)     # [rb, kb, h, r, s, v, 8]
-    full = codes.transpose(0, 3, 1, 4, 2, 5, 6).reshape(n_p, k_p)
+    by = np.asarray(packed, dtype=np.uint8).reshape(n_p // 32, k_p // 128, 2, 2, 32, 2, 2, 4).astype(np.int64)
+    codes = np.concatenate([_sext(by >> 4, 4), _sext(by & 15, 4)], axis=7)     # [rb, kb, sp, h, r, s2, v, 8]
+    full = codes.transpose(0, 4, 1, 2, 5, 3, 6, 7).reshape(n_p, k_p)
     return from_padded(full[:N], cluster_off), full[N:]
