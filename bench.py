@@ -42,6 +42,9 @@ def parse_args():
                     help="chained workloads: store fc1's bf16 output and quantize it with a second kernel "
                          "(rptq_cluster_gemm + rptq_ln_quant) instead of quantizing for the next site in "
                          "fc1's output stage (rptq_cluster_gemm_quant)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the steps (one per input set) into a HIP graph and replay it: the same kernels "
+                         "without per-launch host work (steps is rounded down to a multiple of --sets)")
     ap.add_argument("--library-int8-probe", action="store_true",
                     help="also time the ROCm library's plain GEMMs at the workload's GEMM shapes: int8 x int8 -> int32 "
                          "(torch._int_mm: no unpacking, no per-cluster scales, no output arithmetic) and bf16 (torch.mm: "
@@ -192,10 +195,25 @@ def main():
     torch.cuda.synchronize()
     t0 = torch.cuda.Event(enable_timing=True)
     t1 = torch.cuda.Event(enable_timing=True)
-    t0.record()
-    for i in range(args.steps):
-        step(i)
-    t1.record()
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):           # (the eager warm-up above has done the one-time driver set-up)
+            for i in range(args.sets):
+                step(i)
+        replays = max(1, args.steps // args.sets)
+        args.steps = replays * args.sets
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0.record()
+        for _ in range(replays):
+            graph.replay()
+        t1.record()
+    else:
+        t0.record()
+        for i in range(args.steps):
+            step(i)
+        t1.record()
     torch.cuda.synchronize()
     ms_per_step = t0.elapsed_time(t1) / args.steps
     tokens_per_s = M / (ms_per_step * 1e-3)
@@ -362,7 +380,7 @@ def main():
             args.config, cfg.name, M, bits,
             ";".join("%s(d=%d,g=%d)->%s" % (s.name, s.d, s.g, ",".join("%s %dx%d" % (n, N, s.d) for n, N in s.gemms))
                      for s in cfg.sites)),
-            "input_sets": args.sets, "y_dtype": "bf16", "setup_s": round(t_setup, 2),
+            "input_sets": args.sets, "y_dtype": "bf16", "setup_s": round(t_setup, 2), "hip_graph": bool(args.graph),
             "next_site_quantized_in_output_stage": any(l["next_site"] is not None for s in sites for l in s["lins"])},
         "roofline": roofline,
         "stages": stages,
