@@ -31,11 +31,13 @@ EPS = 1e-5
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: about 3 s of them)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default: a quarter of --steps)")
     ap.add_argument("--ramp-s", type=float, default=1.0,
                     help="seconds of untimed steps before the warmup (the GPU clocks need about a second of load to settle)")
-    ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: OPT-1.3b layer)")
+    ap.add_argument("--config", type=int, default=3,
+                    help="index into BASELINE.json configs (default 3: the OPT-175b prefill layer, the largest "
+                         "single-GPU workload; 4 is the decode layer, 0-2 the smaller ones)")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/weight copies cycled through the steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--unfused", action="store_true",
@@ -45,12 +47,9 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="record the steps (one per input set) into a HIP graph and replay it: the same kernels "
                          "without per-launch host work (steps is rounded down to a multiple of --sets)")
-    ap.add_argument("--library-int8-probe", action="store_true",
-                    help="also time the ROCm library's plain GEMMs at the workload's GEMM shapes: int8 x int8 -> int32 "
-                         "(torch._int_mm: no unpacking, no per-cluster scales, no output arithmetic) and bf16 (torch.mm: "
-                         "what App. A.4's first method would run after de-quantizing); context, not part of the path")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
-                    help="also run one device-to-device copy of this many MiB (a kernel of known traffic, to scale profiler byte counters)")
+                    help="also run one device-to-device copy of this many MiB before the steps: a kernel of known "
+                         "traffic, which a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command uses to scale its byte counters")
     return ap.parse_args()
 
 
@@ -109,7 +108,7 @@ def main():
             del hcal
             prev["row_perm_host"] = cal.perm
             if args.unfused:
-                prev["perm_out"][0] = cal.perm_dev      # fc1's rows leave in this site's cluster order
+                prev["perm_out"][0] = cal.perm      # fc1's rows leave in this site's cluster order
             else:
                 prev["next_site"] = cal                 # ... and padded like it: fc1's output stage quantizes
             Ws = [w.weight_matrix(seed + 500 + li, N, spec.d) for li, (_, N) in enumerate(spec.gemms)]
@@ -190,6 +189,16 @@ def main():
         for i in range(50):
             step(i)
         torch.cuda.synchronize()
+    if args.steps is None:                      # about three seconds of timed steps
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(4):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        args.steps = int(min(2000, max(20, 3000.0 / max(e0.elapsed_time(e1) / 4, 1e-3))))
+    if args.warmup is None:
+        args.warmup = max(5, args.steps // 4)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -266,6 +275,14 @@ def main():
             else:
                 ops = 2.0 * M * lin["N"] * d
                 stage_info["gemm:%s" % lin["name"]] = dict(bound="mfma", work=ops, unit="TOP/s", peak=PEAK_INT8_TOPS, scale=1e-12)
+    # the same peaks from what the box reports: compute units x clock x 8192 int8 ops per clock and
+    # unit (the 32x32x32 int8 MFMA: 65536 ops in 16 passes of 4 clocks on each of 4 matrix cores);
+    # memory clock x bus width x 2 transfers per clock
+    di = rp.rptq_device_info()
+    box = dict(compute_units=di["compute_units"], clock_mhz=round(di["clock_khz"] / 1e3, 1),
+               int8_tops=round(di["compute_units"] * di["clock_khz"] * 1e3 * 8192 / 1e12, 1),
+               memory_clock_mhz=round(di["memory_clock_khz"] / 1e3, 1), memory_bus_bits=di["memory_bus_bits"],
+               hbm_gbs=round(di["memory_clock_khz"] * 1e3 * 2 * di["memory_bus_bits"] / 8 / 1e9, 1))
     dominant = max(stage_avg, key=lambda k: stage_avg[k])
     info = stage_info[dominant]
     achieved = info["work"] / (stage_avg[dominant] * 1e-3) * info["scale"]
@@ -278,7 +295,7 @@ def main():
             traffic = None
     roofline = dict(kernel=dominant, bound=info["bound"], achieved=round(achieved, 3), peak=info["peak"],
                     unit=info["unit"], frac=round(achieved / info["peak"], 4), traffic=traffic,
-                    avg_launch_ms=round(stage_avg[dominant], 5))
+                    avg_launch_ms=round(stage_avg[dominant], 5), peak_from_box=box)
     stages = {}
     for k, ms in stage_avg.items():
         si = stage_info[k]
@@ -292,13 +309,25 @@ def main():
     if not args.no_cpu:
         from oracle import rptq_oracle as o
         cores = len(os.sched_getaffinity(0))
+        if os.environ.get("OMP_NUM_THREADS", "").isdigit():      # numpy's BLAS threads: what the oracle really uses
+            cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
         rows = M
         budget_flops = 4e11                       # keeps the leg to roughly 10-30 s of CPU work
         flops_per_row = sum(2.0 * N * s["spec"].d for s in sites for (_, N) in s["spec"].gemms)
         rows = int(max(16, min(M, budget_flops // flops_per_row)))
         # the oracle keeps the per-cluster integers [g, rows, N] (int64): bound that array to about 2 GB
         rows = int(max(16, min(rows, 2e9 // (8 * max(s["spec"].g * N for s in sites for (_, N) in s["spec"].gemms)))))
-        wqs = [[o.quantize_weights(Wh, s["cal"].perm, s.get("row_perm_host") if li == 0 else None)      # offline work, untimed
+        # offline work, untimed: Eq. 1-2 per output row.  Rows are independent, so the oracle's function is
+        # called on row blocks (bounded memory) from a thread pool.
+        from concurrent.futures import ThreadPoolExecutor
+
+        def quantize_rows(Wh, perm_in, perm_out):
+            order = np.arange(Wh.shape[0]) if perm_out is None else np.asarray(perm_out)
+            blocks = [order[r0:r0 + 2048] for r0 in range(0, len(order), 2048)]
+            with ThreadPoolExecutor(max_workers=cores) as pool:
+                parts = list(pool.map(lambda rws: o.quantize_weights(Wh[rws], perm_in), blocks))
+            return tuple(np.concatenate([p[k] for p in parts]) for k in range(4))
+        wqs = [[quantize_rows(Wh, s["cal"].perm, s.get("row_perm_host") if li == 0 else None)
                 for li, Wh in enumerate(hs["W"])] for s, hs in zip(sites, host_sites)]
         tc = time.perf_counter()
         hidden = None
@@ -317,51 +346,6 @@ def main():
         cpu = dict(value=round(rows / online, 2), unit="tokens/s", cores=cores, kind="oracle",
                    sample="%d of %d tokens, all sites and GEMMs of the workload, numpy float64/int64 oracle "
                           "(offline weight quantization excluded)" % (rows, M), seconds=round(online, 3))
-
-    # ---- context: the vendor library's plain int8 GEMM at the same shapes ---------------------------
-    probe = None
-    if args.library_int8_probe:
-        probe = {}
-        for s in sites:
-            for lin in s["lins"]:
-                K, N = s["spec"].d, lin["N"]
-                a8 = torch.randint(-8, 8, (max(M, 32), K), dtype=torch.int8, device="cuda")
-                b8 = torch.randint(-8, 8, (N, K), dtype=torch.int8, device="cuda").t()     # weights stored [N, K]
-                t_ramp = time.time()
-                while time.time() - t_ramp < 1.0:
-                    for _ in range(20):
-                        torch._int_mm(a8, b8)
-                    torch.cuda.synchronize()
-                reps = []
-                for _ in range(5):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(20):
-                        torch._int_mm(a8, b8)
-                    e1.record()
-                    torch.cuda.synchronize()
-                    reps.append(e0.elapsed_time(e1) / 20)
-                ms = float(np.median(reps))
-                tops = 2.0 * a8.shape[0] * N * K / (ms * 1e-3) * 1e-12
-                a16 = torch.randn((a8.shape[0], K), dtype=torch.bfloat16, device="cuda")
-                b16 = torch.randn((N, K), dtype=torch.bfloat16, device="cuda").t()
-                for _ in range(40):
-                    torch.mm(a16, b16)
-                torch.cuda.synchronize()
-                reps16 = []
-                for _ in range(5):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(20):
-                        torch.mm(a16, b16)
-                    e1.record()
-                    torch.cuda.synchronize()
-                    reps16.append(e0.elapsed_time(e1) / 20)
-                ms16 = float(np.median(reps16))
-                probe["%s %dx%dx%d" % (lin["name"], a8.shape[0], N, K)] = dict(
-                    ms=round(ms, 5), achieved=round(tops, 1), unit="TOP/s", frac=round(tops / PEAK_INT8_TOPS, 4),
-                    bf16_ms=round(ms16, 5))
-                del a8, b8, a16, b16
 
     out = {
         "metric": "tokens/s for LN+quant+cluster-GEMM per layer; % HBM GB/s or int8 MFMA peak",
@@ -386,8 +370,6 @@ def main():
         "stages": stages,
         "cpu_baseline": cpu,
     }
-    if probe is not None:
-        out["library_int8_gemm"] = probe
     print(json.dumps(out))
 
 

@@ -12,8 +12,16 @@
  *  - Every function returns an rptq_status (0 = RPTQ_OK, negative = error).  Arguments
  *    are validated on the host before any HIP call; a failed validation launches nothing.
  *  - The caller owns all memory.  "device" pointers are HIP device memory, 16-byte
- *    aligned; "host" pointers are ordinary host memory.  Except for rptq_calibrate's
- *    own use of its workspace the library keeps no state between calls.
+ *    aligned; "host" pointers are ordinary host memory.  What the library keeps between
+ *    calls, per device and behind a lock (calls may come from several host threads and
+ *    for several devices): the answers of its one-time driver queries (compute-unit
+ *    count, workgroups resident per compute unit and raised dynamic-LDS limit of each
+ *    launch shape) and a status word the offline kernels report bad input through.
+ *    Nothing a result depends on.
+ *  - The first launch of a shape on a device makes those driver queries and must
+ *    therefore happen outside stream capture (RPTQ_ERR_CAPTURE otherwise); every later
+ *    launch of the online entry points (rptq_ln_quant, rptq_cluster_gemm, rptq_cluster_gemm_quant) makes no
+ *    driver call besides the kernel launches, allocates nothing and never synchronizes.
  *  - `stream` is a hipStream_t passed as void*.  Calls are asynchronous on that stream
  *    unless the description says the call synchronizes.
  *  - Cluster tables (cluster_off, scales, zero points) are small host arrays with
@@ -60,6 +68,12 @@ extern "C" {
 #define RPTQ_K_ALIGN 256
 #define RPTQ_N_ALIGN 256
 #define RPTQ_MAX_CHANNELS 32768
+/* Integer headroom of the product kernels: an int8 MFMA operand byte is code << 5, << 4 or
+ * << 0 (|.| <= 128) for activations and code << 4 (|.| <= 128) for weights, and the int32
+ * accumulators hold the running sum over the whole of K_p without ever being cleared, so
+ * |sum| <= 2^14 * K_p.  K_p <= RPTQ_MAX_K_PADDED keeps that below 2^30; every entry point
+ * refuses a cluster table whose K_p is larger (RPTQ_ERR_SHAPE). */
+#define RPTQ_MAX_K_PADDED 65536
 
 typedef enum {
   RPTQ_OK = 0,
@@ -70,7 +84,8 @@ typedef enum {
   RPTQ_ERR_PERM = -5,      /* perm is not a permutation / cluster_off not increasing */
   RPTQ_ERR_RANGE = -6,     /* a zero point or scale is outside what the kernels carry exactly */
   RPTQ_ERR_WORKSPACE = -7, /* workspace too small */
-  RPTQ_ERR_HIP = -8        /* a HIP call failed; see rptq_last_hip_error() */
+  RPTQ_ERR_HIP = -8,       /* a HIP call failed; see rptq_last_hip_error() */
+  RPTQ_ERR_CAPTURE = -9    /* first launch of this shape on this device while the stream is capturing */
 } rptq_status;
 
 enum { RPTQ_DTYPE_BF16 = 0, RPTQ_DTYPE_F32 = 1 };
@@ -127,23 +142,31 @@ int32_t rptq_calibrate(const void* const* x_batches, const int64_t* rows, int32_
  * sums wsum[o,i] = sum_{c in cluster i} wq[o,c] and colterm[o] = sum_i sX_i zX_i wsum[o,i].
  *
  *  gamma,beta device fp32 [d] (NULL,NULL: skip the LayerNorm part)
- *  perm_in    device int32 [K] (K == d), must be a permutation (checked on a host copy
- *             supplied in perm_in_host, host int32 [K])
+ *  perm_in    host int32 [K] (K == d): the site's reorder index; must be a permutation of
+ *             0..K-1 (RPTQ_ERR_PERM).  The library builds perm_pad from it on the host and
+ *             uploads it; no device copy of the index is read.
  *  cluster_off,sX,zX  host [g+1],[g],[g]: the site's calibration result
- *  W          device [N,K] row-major, w_dtype RPTQ_DTYPE_BF16 or RPTQ_DTYPE_F32
- *  perm_out   device int32 [N] or NULL; output row o' is original row perm_out[o'];
- *             -1 makes o' a pad row (weights 0, sW = 1, zW = 0, so Y[:,o'] = 0).  Passing the
- *             *next* site's perm_pad with N = its K_p lays the product's columns out as that
- *             site's padded cluster-order positions (what rptq_cluster_gemm_quant needs).
+ *  W          device [w_rows,K] row-major, w_dtype RPTQ_DTYPE_BF16 or RPTQ_DTYPE_F32; NULL: only
+ *             the LayerNorm part / perm_pad
+ *  w_rows     rows of W.  Without perm_out, N <= w_rows is required.
+ *  perm_out   host int32 [N] or NULL; output row o' is original row perm_out[o'], which must lie
+ *             in 0..w_rows-1, or be -1 (RPTQ_ERR_PERM otherwise); -1 makes o' a pad row (weights
+ *             0, sW = 1, zW = 0, so Y[:,o'] = 0).  Passing the *next* site's perm_pad with N = its
+ *             K_p lays the product's columns out as that site's padded cluster-order positions
+ *             (what rptq_cluster_gemm_quant needs).
  *  perm_pad   device int32 [K_p] out: source channel of each padded position, -1 = pad
  *  gamma_pad,beta_pad device fp32 [K_p] out (untouched when gamma == NULL)
  *  Wq_packed  device out, rptq_weight_bytes(N, K_p)
  *  sW device fp32 [N], zW device int32 [N], wsum device int32 [N,g], colterm device fp32 [N]
+ * Offline call: synchronizes the stream before returning (so that it can report what the
+ * kernels found), cannot be captured.  RPTQ_ERR_RANGE when a weight is not finite or a row's
+ * range gives a scale that is not a normal fp32 number; the outputs are then unspecified.
  */
 int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
-                          const int32_t* perm_in, const int32_t* perm_in_host,
+                          const int32_t* perm_in,
                           const int32_t* cluster_off, int32_t g, const float* sX, const int32_t* zX,
-                          const void* W, int32_t w_dtype, int32_t N, int32_t K, const int32_t* perm_out,
+                          const void* W, int32_t w_dtype, int32_t w_rows, int32_t N, int32_t K,
+                          const int32_t* perm_out,
                           int32_t* perm_pad, float* gamma_pad, float* beta_pad,
                           void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm,
                           void* stream);
@@ -164,6 +187,8 @@ int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
  *  xsum       device int32 [M,g] out or NULL: per-cluster code sums
  *  rowterm    device fp32 [M] out or NULL: sum_i s_i (xsum[t,i] - n_i z_i), the row sum of
  *             the de-quantized activation, which the product's zero-point term needs
+ * Inputs must be finite: a NaN or infinity in x gives unspecified codes for its row (no
+ * fault, no error).
  * Shapes the kernel does not cover return RPTQ_ERR_SHAPE before anything is launched: a
  * workgroup holds at most 960 unit threads of at most 2 (LayerNorm; 1 at 3 bits) or 4 (2)
  * units of 8 (16) codes, i.e. K_p <= 15360 with LayerNorm and K_p <= 30720 without, and two
@@ -246,6 +271,11 @@ int32_t rptq_channel_minmax(const void* const* x_batches, const int64_t* rows, i
 int32_t rptq_cluster_channels(const float* ch_min, const float* ch_max, int32_t d, int32_t g, int32_t bits,
                               uint64_t seed, int32_t max_iter, int32_t* assign, int32_t* perm,
                               int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff);
+
+/* What the current device reports about itself, for roofline denominators: compute units,
+ * engine clock and memory clock in kHz, memory bus width in bits (each may be NULL). */
+int32_t rptq_device_info(int32_t* compute_units, int32_t* clock_khz, int32_t* memory_clock_khz,
+                         int32_t* memory_bus_bits);
 
 const char* rptq_strerror(int32_t status);
 int32_t rptq_last_hip_error(void);

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     rptq_cluster_gemm_partials,
     rptq_unpack_codes,
     rptq_unpack_weights,
+    rptq_device_info,
     rptq_strerror,
     rptq_version,
     EXPORTED_SYMBOLS,

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = (
     "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_cluster_gemm",
     "rptq_cluster_gemm_quant", "rptq_cluster_gemm_quant_workspace_bytes",
     "rptq_cluster_gemm_partials", "rptq_unpack_codes", "rptq_unpack_weights", "rptq_channel_minmax",
-    "rptq_cluster_channels", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
+    "rptq_cluster_channels", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
 )
 
 _LIB = None
@@ -61,7 +61,7 @@ def load_library():
         "rptq_calibrate_workspace_bytes": (sz, [i32]),
         "rptq_calibrate": (i32, [vp, vp, i32, i32, vp, vp, f32, i32, i32, i32, u64, i32,
                                  vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
-        "rptq_fold_reorder": (i32, [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32, i32, vp,
+        "rptq_fold_reorder": (i32, [vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp,
                                     vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "rptq_ln_quant": (i32, [vp, i64, i32, vp, vp, f32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp]),
         "rptq_cluster_gemm": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, vp]),
@@ -73,6 +73,7 @@ def load_library():
         "rptq_unpack_weights": (i32, [vp, i32, vp, i32, vp, vp]),
         "rptq_channel_minmax": (i32, [vp, vp, i32, i32, vp, vp, f32, i32, vp, vp, vp, sz, vp]),
         "rptq_cluster_channels": (i32, [vp, vp, i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_device_info": (i32, [vp, vp, vp, vp]),
         "rptq_strerror": (C.c_char_p, [i32]),
         "rptq_last_hip_error": (i32, []),
         "rptq_version": (C.c_char_p, []),
@@ -127,6 +128,13 @@ def rptq_strerror(status: int) -> str:
 
 def rptq_version() -> str:
     return load_library().rptq_version().decode()
+
+
+def rptq_device_info() -> dict:
+    vals = [C.c_int32(0) for _ in range(4)]
+    _check(load_library().rptq_device_info(*[C.byref(v) for v in vals]), "rptq_device_info")
+    return dict(compute_units=vals[0].value, clock_khz=vals[1].value, memory_clock_khz=vals[2].value,
+                memory_bus_bits=vals[3].value)
 
 
 def rptq_padded_k(cluster_off) -> int:
@@ -226,24 +234,31 @@ def rptq_calibrate(x_batches, gamma, beta, eps: float, relu: bool, g: int, bits:
                 s=s[:ge].copy(), inv_s=inv_s[:ge].copy(), z=z[:ge].copy(), g_eff=ge)
 
 
-def rptq_fold_reorder(gamma, beta, d: int, perm_in_dev, perm_in_host, cluster_off, sX, zX, W, N: int, K: int,
+def rptq_fold_reorder(gamma, beta, d: int, perm_in, cluster_off, sX, zX, W, N: int, K: int,
                       perm_out, perm_pad, gamma_pad, beta_pad, Wq_packed, sW, zW, wsum, colterm, stream=None):
+    """perm_in / perm_out are host index arrays (numpy); W, the outputs and gamma/beta are device tensors."""
     import torch
     off, poff = _host(cluster_off, np.int32)
     g = len(off) - 1
-    ph, pph = _host(perm_in_host, np.int32)
+    ph, pph = _host(perm_in, np.int32)
     sx, psx = _host(sX if sX is not None else np.ones(g), np.float32)
     zx, pzx = _host(zX if zX is not None else np.zeros(g), np.int32)
-    w_dtype = DTYPE_BF16
+    po, ppo = (None, None) if perm_out is None else _host(perm_out, np.int32)
+    w_dtype, w_rows = DTYPE_BF16, 0
     if W is not None:
         if W.dtype == torch.float32:
             w_dtype = DTYPE_F32
         elif W.dtype != torch.bfloat16:
             raise ValueError("W must be bf16 or fp32")
+        if W.dim() != 2 or W.shape[1] != K:
+            raise ValueError("W must be [rows, K]")
+        w_rows = W.shape[0]
+        if po is not None and po.shape[0] != N:
+            raise ValueError("perm_out must have N entries")
     st = load_library().rptq_fold_reorder(
         _dev(gamma, torch.float32, True), _dev(beta, torch.float32, True), d,
-        _dev(perm_in_dev, torch.int32), pph, poff, g, psx, pzx,
-        _dev(W, None, True), w_dtype, N, K, _dev(perm_out, torch.int32, True),
+        pph, poff, g, psx, pzx,
+        _dev(W, None, True), w_dtype, w_rows, N, K, ppo,
         _dev(perm_pad, torch.int32), _dev(gamma_pad, torch.float32, True), _dev(beta_pad, torch.float32, True),
         _dev(Wq_packed, None, True), _dev(sW, torch.float32, True), _dev(zW, torch.int32, True),
         _dev(wsum, torch.int32, True), _dev(colterm, torch.float32, True), _stream(stream))

@@ -90,13 +90,14 @@ int32_t rptq_calibrate(const void* const* x_batches, const int64_t* rows, int32_
 }
 
 int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
-                          const int32_t* perm_in, const int32_t* perm_in_host,
+                          const int32_t* perm_in,
                           const int32_t* cluster_off, int32_t g, const float* sX, const int32_t* zX,
-                          const void* W, int32_t w_dtype, int32_t N, int32_t K, const int32_t* perm_out,
+                          const void* W, int32_t w_dtype, int32_t w_rows, int32_t N, int32_t K,
+                          const int32_t* perm_out,
                           int32_t* perm_pad, float* gamma_pad, float* beta_pad,
                           void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm,
                           void* stream) {
-  if (!perm_in || !perm_in_host || !perm_pad) return RPTQ_ERR_NULL;
+  if (!perm_in || !perm_pad) return RPTQ_ERR_NULL;
   if ((gamma == nullptr) != (beta == nullptr)) return RPTQ_ERR_NULL;
   if (gamma && (!gamma_pad || !beta_pad)) return RPTQ_ERR_NULL;
   if (W && (!Wq_packed || !sW || !zW || !wsum || !colterm || !sX || !zX)) return RPTQ_ERR_NULL;
@@ -104,19 +105,27 @@ int32_t rptq_fold_reorder(const float* gamma, const float* beta, int32_t d,
   if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
   if (d < 1 || geom.k != d) return RPTQ_ERR_SHAPE;
   if (W) {
-    if (K != d || N < 1) return RPTQ_ERR_SHAPE;
+    if (K != d || N < 1 || w_rows < 1) return RPTQ_ERR_SHAPE;
+    if (!perm_out && N > w_rows) return RPTQ_ERR_SHAPE;
     if (w_dtype != RPTQ_DTYPE_BF16 && w_dtype != RPTQ_DTYPE_F32) return RPTQ_ERR_SHAPE;
     for (int i = 0; i < g; ++i) {
       if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
       if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
     }
+    if (perm_out)                                    // every source row exists, or the entry is a pad row
+      for (int32_t o = 0; o < N; ++o)
+        if (perm_out[o] < -1 || perm_out[o] >= w_rows) return RPTQ_ERR_PERM;
   }
-  if (int32_t st = check_permutation(perm_in_host, d)) return st;
-  if (!aligned16(perm_in) || !aligned16(perm_pad) || !aligned16(gamma) || !aligned16(beta) || !aligned16(gamma_pad) ||
+  if (int32_t st = check_permutation(perm_in, d)) return st;
+  if (!aligned16(perm_pad) || !aligned16(gamma) || !aligned16(beta) || !aligned16(gamma_pad) ||
       !aligned16(beta_pad) || !aligned16(W) || !aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) ||
-      !aligned16(wsum) || !aligned16(colterm) || !aligned16(perm_out))
+      !aligned16(wsum) || !aligned16(colterm))
     return RPTQ_ERR_ALIGN;
-  return launch_fold(gamma, beta, perm_in, geom, sX, zX, W, w_dtype, N, perm_out, perm_pad, gamma_pad, beta_pad,
+  // source channel of every padded position (-1 = pad), from the validated index
+  std::vector<int32_t> pad(static_cast<size_t>(geom.k_padded), -1);
+  for (int i = 0; i < g; ++i)
+    for (int32_t j = geom.off[i]; j < geom.off[i + 1]; ++j) pad[geom.pad_off[i] + (j - geom.off[i])] = perm_in[j];
+  return launch_fold(gamma, beta, pad.data(), geom, sX, zX, W, w_dtype, N, perm_out, perm_pad, gamma_pad, beta_pad,
                      Wq_packed, sW, zW, wsum, colterm, static_cast<hipStream_t>(stream));
 }
 

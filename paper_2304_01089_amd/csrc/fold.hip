@@ -10,22 +10,19 @@
 
 namespace rptq {
 
-__global__ void fold_ln_kernel(const float* gamma, const float* beta, const int32_t* perm_in, ClusterGeom geom,
-                               int32_t* perm_pad, float* gamma_pad, float* beta_pad) {
+// What the offline kernels report back: bit 0 = a weight is not finite, bit 1 = a row's Eq. 2
+// scale is not a normal fp32 number.  One word per device; cleared and read by launch_fold.
+__device__ int32_t g_fold_status;
+
+__global__ void fold_status_clear_kernel() { g_fold_status = 0; }
+
+__global__ void fold_ln_kernel(const float* gamma, const float* beta, const int32_t* perm_pad, int32_t k_padded,
+                               float* gamma_pad, float* beta_pad) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= geom.k_padded) return;
-  int c = -1;
-  if (j < geom.pad_off[geom.g]) {
-    int ci = 0;
-    for (int i = 1; i < geom.g; ++i) ci += (j >= geom.pad_off[i]) ? 1 : 0;
-    const int local = j - geom.pad_off[ci];
-    if (local < geom.off[ci + 1] - geom.off[ci]) c = perm_in[geom.off[ci] + local];
-  }
-  perm_pad[j] = c;
-  if (gamma) {
-    gamma_pad[j] = c >= 0 ? gamma[c] : 0.0f;
-    beta_pad[j] = c >= 0 ? beta[c] : 0.0f;
-  }
+  if (j >= k_padded) return;
+  const int c = perm_pad[j];
+  gamma_pad[j] = c >= 0 ? gamma[c] : 0.0f;
+  beta_pad[j] = c >= 0 ? beta[c] : 0.0f;
 }
 
 // Byte offset of the dword holding padded columns 8u..8u+7 of output row o.
@@ -42,7 +39,7 @@ struct FoldArgs {
   int32_t w_bf16;
   int32_t N;
   int32_t n_padded;
-  const int32_t* perm_out;
+  int32_t has_perm_out;          // the caller's output index was uploaded into zW[0..N)
   const int32_t* perm_pad;
   uint8_t* Wq;
   float* sW;
@@ -69,11 +66,14 @@ __global__ void __launch_bounds__(256) fold_weight_kernel(FoldArgs a, ClusterGeo
       *reinterpret_cast<uint32_t*>(a.Wq + weight_dword_offset(o, u, geom.k_padded)) = 0u;
     return;
   }
-  const int64_t src_row = a.perm_out ? a.perm_out[o] : o;
+  // (zW[o] carries the validated source row of output o until this workgroup overwrites it with
+  // the row's zero point: every thread reads it here, thread 0 writes behind a barrier)
+  const int64_t src_row = a.has_perm_out ? a.zW[o] : o;
   if (src_row < 0) {                               // a pad row of the output layout: weights 0, s = 1, z = 0
     for (int u = tid; u < n_units; u += blockDim.x)
       *reinterpret_cast<uint32_t*>(a.Wq + weight_dword_offset(o, u, geom.k_padded)) = 0u;
     if (tid < geom.g) a.wsum[static_cast<int64_t>(o) * geom.g + tid] = 0;
+    __syncthreads();
     if (tid == 0) {
       a.sW[o] = 1.0f;
       a.zW[o] = 0;
@@ -87,11 +87,14 @@ __global__ void __launch_bounds__(256) fold_weight_kernel(FoldArgs a, ClusterGeo
 
   // ---- Eq. 2 over the whole row ---------------------------------------------------------
   float lo = __builtin_huge_valf(), hi = -__builtin_huge_valf();
+  bool bad = false;
   for (int c = tid; c < geom.k; c += blockDim.x) {
     const float w = wval(c);
+    bad |= !(fabsf(w) <= 3.4028234664e38f);         // NaN or infinity (min/max would skip a NaN)
     lo = fminf(lo, w);
     hi = fmaxf(hi, w);
   }
+  if (bad) atomicOr(&g_fold_status, 1);
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
     lo = fminf(lo, __shfl_xor(lo, m, kWave));
@@ -115,6 +118,7 @@ __global__ void __launch_bounds__(256) fold_weight_kernel(FoldArgs a, ClusterGeo
       zz = -rint((h + l) / (2.0 * s64));
     }
     const float s32 = static_cast<float>(s64);
+    if (!(s32 >= 1.17549435e-38f && s32 <= 3.4028234664e38f)) atomicOr(&g_fold_status, 2);
     sh_inv = static_cast<float>(1.0 / static_cast<double>(s32));
     sh_z = static_cast<int32_t>(zz);
     a.sW[o] = s32;
@@ -172,20 +176,29 @@ __global__ void unpack_weights_kernel(const uint8_t* Wq, int N, ClusterGeom geom
   }
 }
 
-int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_in, const ClusterGeom& geom,
+int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_pad_host, const ClusterGeom& geom,
                     const float* sX, const int32_t* zX, const void* W, int32_t w_dtype, int32_t N,
-                    const int32_t* perm_out, int32_t* perm_pad, float* gamma_pad, float* beta_pad,
+                    const int32_t* perm_out_host, int32_t* perm_pad, float* gamma_pad, float* beta_pad,
                     void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm, hipStream_t st) {
-  hipLaunchKernelGGL(fold_ln_kernel, dim3((geom.k_padded + 255) / 256), dim3(256), 0, st, gamma, beta, perm_in, geom,
-                     perm_pad, gamma_pad, beta_pad);
-  RPTQ_HIP(hipGetLastError());
-  if (!W) return RPTQ_OK;
+  // the index arrays were validated on the host; they are uploaded from there, so what the
+  // kernels read is what was checked
+  RPTQ_HIP(hipMemcpyAsync(perm_pad, perm_pad_host, sizeof(int32_t) * geom.k_padded, hipMemcpyHostToDevice, st));
+  if (gamma) {
+    hipLaunchKernelGGL(fold_ln_kernel, dim3((geom.k_padded + 255) / 256), dim3(256), 0, st, gamma, beta, perm_pad,
+                       geom.k_padded, gamma_pad, beta_pad);
+    RPTQ_HIP(hipGetLastError());
+  }
+  if (!W) {
+    RPTQ_HIP(hipStreamSynchronize(st));            // perm_pad_host belongs to the caller's frame
+    return RPTQ_OK;
+  }
+  if (perm_out_host) RPTQ_HIP(hipMemcpyAsync(zW, perm_out_host, sizeof(int32_t) * N, hipMemcpyHostToDevice, st));
   FoldArgs a;
   a.W = W;
   a.w_bf16 = (w_dtype == RPTQ_DTYPE_BF16);
   a.N = N;
   a.n_padded = (N + RPTQ_N_ALIGN - 1) / RPTQ_N_ALIGN * RPTQ_N_ALIGN;
-  a.perm_out = perm_out;
+  a.has_perm_out = perm_out_host != nullptr;
   a.perm_pad = perm_pad;
   a.Wq = static_cast<uint8_t*>(Wq_packed);
   a.sW = sW;
@@ -195,9 +208,14 @@ int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_i
   ScaleTab tab;
   for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i)
     tab.sz[i] = i < geom.g ? static_cast<double>(sX[i]) * static_cast<double>(zX[i]) : 0.0;
+  hipLaunchKernelGGL(fold_status_clear_kernel, dim3(1), dim3(1), 0, st);
+  RPTQ_HIP(hipGetLastError());
   hipLaunchKernelGGL(fold_weight_kernel, dim3(a.n_padded), dim3(256), 0, st, a, geom, tab);
   RPTQ_HIP(hipGetLastError());
-  return RPTQ_OK;
+  int32_t status = 0;
+  RPTQ_HIP(hipMemcpyFromSymbolAsync(&status, HIP_SYMBOL(g_fold_status), sizeof(status), 0, hipMemcpyDeviceToHost, st));
+  RPTQ_HIP(hipStreamSynchronize(st));
+  return status ? RPTQ_ERR_RANGE : RPTQ_OK;
 }
 
 int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st) {

@@ -596,8 +596,8 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuant
   constexpr size_t terms = PARTIALS ? 0 : static_cast<size_t>(3 * BN + BM) * 4;     // output-stage vectors of the tile
   constexpr size_t shmem = (pipe > stage ? pipe : stage) + terms;
   auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, OUT>;
-  static int lds_granted[kMaxDevices] = {0};
-  if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, lds_granted)) return st_lds;
+  static LdsGrant lds_granted;
+  if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, &lds_granted, st)) return st_lds;
   GemmArgs b = a;
   b.tiles_n = (a.N + BN - 1) / BN;
   b.tiles_m = static_cast<int32_t>((a.M + BM - 1) / BM);

@@ -23,6 +23,78 @@ int32_t hip_fail(hipError_t e) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---- per-device memo of one-time driver answers ---------------------------------------------
+std::mutex& state_mutex() {
+  static std::mutex m;
+  return m;
+}
+
+int32_t current_device(int* dev) {
+  RPTQ_HIP(hipGetDevice(dev));
+  return RPTQ_OK;
+}
+
+int32_t require_not_capturing(hipStream_t st) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  RPTQ_HIP(hipStreamIsCapturing(st, &cs));
+  return cs == hipStreamCaptureStatusNone ? RPTQ_OK : RPTQ_ERR_CAPTURE;
+}
+
+int32_t device_compute_units(hipStream_t st, int* cus) {
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (int32_t s = current_device(&dev)) return s;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  std::lock_guard<std::mutex> lock(state_mutex());
+  if (tracked && cached[dev] > 0) {
+    *cus = cached[dev];
+    return RPTQ_OK;
+  }
+  if (int32_t s = require_not_capturing(st)) return s;
+  int n = 0;
+  RPTQ_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+  if (n < 1) n = 1;
+  if (tracked) cached[dev] = n;
+  *cus = n;
+  return RPTQ_OK;
+}
+
+int32_t ensure_dynamic_lds(const void* kern, size_t bytes, LdsGrant* granted, hipStream_t st) {
+  if (bytes <= 64 * 1024) return RPTQ_OK;
+  int dev = 0;
+  if (int32_t s = current_device(&dev)) return s;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  std::lock_guard<std::mutex> lock(state_mutex());
+  if (tracked && granted->bytes[dev] >= static_cast<int>(bytes)) return RPTQ_OK;
+  if (int32_t s = require_not_capturing(st)) return s;
+  RPTQ_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)));
+  if (tracked) granted->bytes[dev] = static_cast<int>(bytes);
+  return RPTQ_OK;
+}
+
+int32_t resident_workgroups(const void* kern, int threads, size_t shmem, OccupancyMemo* memo, hipStream_t st,
+                            int* per_cu) {
+  int dev = 0;
+  if (int32_t s = current_device(&dev)) return s;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  std::lock_guard<std::mutex> lock(state_mutex());
+  if (tracked && memo->per_cu[dev] > 0 && memo->threads[dev] == threads && memo->shmem[dev] == shmem) {
+    *per_cu = memo->per_cu[dev];
+    return RPTQ_OK;
+  }
+  if (int32_t s = require_not_capturing(st)) return s;
+  int n = 0;
+  RPTQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, shmem));
+  if (n < 1) n = 1;
+  if (tracked) {
+    memo->threads[dev] = threads;
+    memo->shmem[dev] = shmem;
+    memo->per_cu[dev] = n;
+  }
+  *per_cu = n;
+  return RPTQ_OK;
+}
+
 int32_t check_bits(int32_t bits) { return (bits == 3 || bits == 4 || bits == 8) ? RPTQ_OK : RPTQ_ERR_BITS; }
 
 int32_t check_clusters(const int32_t* cluster_off, int32_t g, ClusterGeom* geom) {
@@ -40,12 +112,16 @@ int32_t check_clusters(const int32_t* cluster_off, int32_t g, ClusterGeom* geom)
     int32_t n = cluster_off[i + 1] - cluster_off[i];
     padded += (n + kGroup - 1) / kGroup * kGroup;
   }
+  const int64_t k_padded = (padded + RPTQ_K_ALIGN - 1) / RPTQ_K_ALIGN * RPTQ_K_ALIGN;
+  // int32 headroom of the product kernels: |running sum| <= 2^14 * K_p must stay below 2^30
+  static_assert(static_cast<int64_t>(RPTQ_MAX_K_PADDED) * (1 << 14) <= (int64_t{1} << 30), "accumulator headroom");
+  if (k_padded > RPTQ_MAX_K_PADDED) return RPTQ_ERR_SHAPE;
   if (geom) {
     geom->g = g;
     geom->k = cluster_off[g];
     geom->off[g] = cluster_off[g];
     geom->pad_off[g] = static_cast<int32_t>(padded);
-    geom->k_padded = static_cast<int32_t>((padded + RPTQ_K_ALIGN - 1) / RPTQ_K_ALIGN * RPTQ_K_ALIGN);
+    geom->k_padded = static_cast<int32_t>(k_padded);
     for (int i = g + 1; i <= RPTQ_MAX_CLUSTERS; ++i) {
       geom->off[i] = geom->off[g];
       geom->pad_off[i] = geom->pad_off[g];
@@ -266,6 +342,30 @@ int32_t rptq_cluster_channels(const float* ch_min, const float* ch_max, int32_t 
   return cluster_channels(ch_min, ch_max, d, g, bits, seed, max_iter, assign, perm, cluster_off, s, inv_s, z, g_eff);
 }
 
+int32_t rptq_device_info(int32_t* compute_units, int32_t* clock_khz, int32_t* memory_clock_khz,
+                         int32_t* memory_bus_bits) {
+  int dev = 0;
+  RPTQ_HIP(hipGetDevice(&dev));
+  int v = 0;
+  if (compute_units) {
+    RPTQ_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+    *compute_units = v;
+  }
+  if (clock_khz) {
+    RPTQ_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeClockRate, dev));
+    *clock_khz = v;
+  }
+  if (memory_clock_khz) {
+    RPTQ_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMemoryClockRate, dev));
+    *memory_clock_khz = v;
+  }
+  if (memory_bus_bits) {
+    RPTQ_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMemoryBusWidth, dev));
+    *memory_bus_bits = v;
+  }
+  return RPTQ_OK;
+}
+
 const char* rptq_strerror(int32_t status) {
   switch (status) {
     case RPTQ_OK: return "ok";
@@ -277,6 +377,7 @@ const char* rptq_strerror(int32_t status) {
     case RPTQ_ERR_RANGE: return "zero point or scale outside the exactly representable range";
     case RPTQ_ERR_WORKSPACE: return "workspace too small";
     case RPTQ_ERR_HIP: return "a HIP call failed (see rptq_last_hip_error)";
+    case RPTQ_ERR_CAPTURE: return "first launch of this shape on this device must happen outside stream capture";
     default: return "unknown status";
   }
 }

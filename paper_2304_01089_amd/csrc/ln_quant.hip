@@ -405,20 +405,13 @@ template <int BITS, int NUNIT, int NCH, bool LN>
 static int32_t launch_kernel(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, int threads,
                              int64_t want_grid, int lds_per_cu, size_t shmem, hipStream_t st) {
   auto kern = ln_quant_kernel<BITS, NUNIT, NCH, LN>;
-  static int lds_granted[kMaxDevices] = {0};
-  if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, lds_granted)) return st_lds;
-  // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round.
-  // (the last answer is kept: a serving loop asks for the same launch shape again and again)
-  static int cached_threads = -1, cached_per_cu = 0;
-  static size_t cached_shmem = 0;
-  int per_cu = cached_per_cu;
-  if (cached_threads != threads || cached_shmem != shmem) {
-    RPTQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, shmem));
-    if (per_cu < 1) per_cu = 1;
-    cached_per_cu = per_cu;
-    cached_shmem = shmem;
-    cached_threads = threads;
-  }
+  static LdsGrant lds_granted;
+  if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, &lds_granted, st)) return st_lds;
+  // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round
+  static OccupancyMemo occupancy;
+  int per_cu = 1;
+  if (int32_t st_occ = resident_workgroups(reinterpret_cast<const void*>(kern), threads, shmem, &occupancy, st, &per_cu))
+    return st_occ;
   (void)lds_per_cu;
   const int64_t grid = std::min<int64_t>(a.M, want_grid * per_cu);
   hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(threads), shmem, st, a, geom, qt);
@@ -500,12 +493,8 @@ int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_
   if (best_t == 0) return RPTQ_ERR_SHAPE;
   const int nch = (a.chunks + best_t - 1) / best_t;          // 1, 2 or 3..4 (run as 4)
 
-  static int cus = 0;                              // compute units of the device (one device type per process)
-  if (cus == 0) {
-    int dev = 0;
-    RPTQ_HIP(hipGetDevice(&dev));
-    RPTQ_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  }
+  int cus = 0;                                     // compute units of the current device
+  if (int32_t st_cu = device_compute_units(st, &cus)) return st_cu;
   const int lds_cu = 160 * 1024;
   a.ring = 3;
   LnLds lay = ln_lds_layout(d, 3, best_t);

@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "rptq.h"
 
 namespace rptq {
@@ -46,21 +48,36 @@ int32_t hip_fail(hipError_t e);
     if (e_ != hipSuccess) return ::rptq::hip_fail(e_);   \
   } while (0)
 
+// ---- what the library remembers between calls (host.cpp) ---------------------------------
+// One-time driver answers are kept per device (index of the current device at the call) in
+// small tables guarded by one mutex; a device index beyond kMaxDevices is simply not cached.
+constexpr int kMaxDevices = 64;
+std::mutex& state_mutex();
+// Index of the current device (hipGetDevice); RPTQ_ERR_HIP on failure.
+int32_t current_device(int* dev);
+// RPTQ_ERR_CAPTURE when `st` is recording a graph: a driver query may not run then.
+int32_t require_not_capturing(hipStream_t st);
+// Compute units of the current device (cached).
+int32_t device_compute_units(hipStream_t st, int* cus);
+
 // Raises a kernel's dynamic-LDS limit when a launch needs more than the default 64 KiB.  The
 // driver call is made once per device and size (granted[] belongs to one kernel: a static
 // array of kMaxDevices zeros in its launcher), so that repeated launches, and launches under
 // stream capture, make no driver call at all.
-constexpr int kMaxDevices = 64;
-inline int32_t ensure_dynamic_lds(const void* kern, size_t bytes, int* granted) {
-  if (bytes <= 64 * 1024) return RPTQ_OK;
-  int dev = 0;
-  RPTQ_HIP(hipGetDevice(&dev));
-  const bool tracked = dev >= 0 && dev < kMaxDevices;
-  if (tracked && granted[dev] >= static_cast<int>(bytes)) return RPTQ_OK;
-  RPTQ_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)));
-  if (tracked) granted[dev] = static_cast<int>(bytes);
-  return RPTQ_OK;
-}
+struct LdsGrant {
+  int bytes[kMaxDevices] = {};
+};
+int32_t ensure_dynamic_lds(const void* kern, size_t bytes, LdsGrant* granted, hipStream_t st);
+
+// Workgroups of one launch shape resident per compute unit (occupancy query), cached per
+// device for the last shape asked: a serving loop asks for the same shape again and again.
+struct OccupancyMemo {
+  int threads[kMaxDevices] = {};
+  size_t shmem[kMaxDevices] = {};
+  int per_cu[kMaxDevices] = {};
+};
+int32_t resident_workgroups(const void* kern, int threads, size_t shmem, OccupancyMemo* memo, hipStream_t st,
+                            int* per_cu);
 
 // Host clustering (host.cpp), exposed through rptq_cluster_channels.
 int32_t cluster_channels(const float* ch_min, const float* ch_max, int32_t d, int32_t g, int32_t bits,
@@ -71,9 +88,12 @@ int32_t cluster_channels(const float* ch_min, const float* ch_max, int32_t d, in
 int32_t launch_channel_minmax(const void* const* x_batches, const int64_t* rows, int32_t n_batches, int32_t d,
                               const float* gamma, const float* beta, float eps, int32_t relu,
                               float* ch_min_dev, float* ch_max_dev, uint32_t* keys, hipStream_t st);
-int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_in, const ClusterGeom& geom,
+// perm_pad_host: [k_padded] built by the caller; perm_out_host: [N] or NULL (uploaded through zW).
+// Synchronizes `st` and returns RPTQ_ERR_RANGE when the weight kernel met a non-finite weight
+// or a scale that is not a normal fp32 number.
+int32_t launch_fold(const float* gamma, const float* beta, const int32_t* perm_pad_host, const ClusterGeom& geom,
                     const float* sX, const int32_t* zX, const void* W, int32_t w_dtype, int32_t N,
-                    const int32_t* perm_out, int32_t* perm_pad, float* gamma_pad, float* beta_pad,
+                    const int32_t* perm_out_host, int32_t* perm_pad, float* gamma_pad, float* beta_pad,
                     void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* colterm, hipStream_t st);
 int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_pad, const float* beta_pad,
                         float eps, int32_t relu, const int32_t* perm_pad, const ClusterGeom& geom,

@@ -25,8 +25,8 @@ class Calibration:
     z: np.ndarray
     g_eff: int
     k_padded: int
-    perm_dev: object = None
-    perm_pad: object = None
+    perm_pad: object = None          # device int32 [K_p]
+    perm_pad_host: np.ndarray = None
     gamma_pad: object = None
     beta_pad: object = None
 
@@ -47,13 +47,13 @@ def calibrate_site(x_batches, gamma, beta, eps, relu, g, bits, seed=0, max_iter=
     d = x_batches[0].shape[1]
     cal = Calibration(d=d, bits=bits, k_padded=B.rptq_padded_k(res["cluster_off"]), **res)
     dev = x_batches[0].device
-    cal.perm_dev = torch.from_numpy(cal.perm).to(dev)
     cal.perm_pad = torch.empty(cal.k_padded, dtype=torch.int32, device=dev)
     if gamma is not None:
         cal.gamma_pad = torch.empty(cal.k_padded, dtype=torch.float32, device=dev)
         cal.beta_pad = torch.empty(cal.k_padded, dtype=torch.float32, device=dev)
-    B.rptq_fold_reorder(gamma, beta, d, cal.perm_dev, cal.perm, cal.cluster_off, None, None, None, 0, d, None,
+    B.rptq_fold_reorder(gamma, beta, d, cal.perm, cal.cluster_off, None, None, None, 0, d, None,
                         cal.perm_pad, cal.gamma_pad, cal.beta_pad, None, None, None, None, None)
+    cal.perm_pad_host = cal.perm_pad.cpu().numpy()
     return cal
 
 
@@ -66,23 +66,23 @@ def identity_site(cal: Calibration) -> Calibration:
     out = copy.copy(cal)
     ident = np.arange(cal.d, dtype=np.int32)
     out.perm = ident
-    out.perm_dev = torch.from_numpy(ident).to(cal.perm_dev.device)
     out.perm_pad = torch.empty_like(cal.perm_pad)
     out.gamma_pad = None
     out.beta_pad = None
-    B.rptq_fold_reorder(None, None, cal.d, out.perm_dev, ident, cal.cluster_off, None, None, None, 0, cal.d, None,
+    B.rptq_fold_reorder(None, None, cal.d, ident, cal.cluster_off, None, None, None, 0, cal.d, None,
                         out.perm_pad, None, None, None, None, None, None, None)
+    out.perm_pad_host = out.perm_pad.cpu().numpy()
     return out
 
 
 def fold_linear(cal: Calibration, W, perm_out=None, next_site: Optional[Calibration] = None) -> FoldedLinear:
-    """perm_out: reorder index of the layer's output (rows of W).  next_site: lay the rows out
+    """perm_out: reorder index of the layer's output (rows of W), a host array.  next_site: lay the rows out
     as that site's padded cluster-order positions instead (pad rows are zero), which is what
     cluster_gemm_quant needs; the layer then has next_site.k_padded outputs."""
     import torch
     N, K = W.shape
     if next_site is not None:
-        perm_out = next_site.perm_pad
+        perm_out = next_site.perm_pad_host
         N = next_site.k_padded
     dev = W.device
     out = FoldedLinear(
@@ -92,7 +92,7 @@ def fold_linear(cal: Calibration, W, perm_out=None, next_site: Optional[Calibrat
         zW=torch.empty(N, dtype=torch.int32, device=dev),
         wsum=torch.empty((N, cal.g_eff), dtype=torch.int32, device=dev),
         colterm=torch.empty(N, dtype=torch.float32, device=dev))
-    B.rptq_fold_reorder(None, None, cal.d, cal.perm_dev, cal.perm, cal.cluster_off, cal.s, cal.z, W, N, K, perm_out,
+    B.rptq_fold_reorder(None, None, cal.d, cal.perm, cal.cluster_off, cal.s, cal.z, W, N, K, perm_out,
                         cal.perm_pad, None, None, out.Wq, out.sW, out.zW, out.wsum, out.colterm)
     return out
 

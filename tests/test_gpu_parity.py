@@ -74,6 +74,11 @@ CASES = {
     # input chunks and four units per thread
     "wide_relu": dict(seed=19, d=24576, M=9, g=8, bits=4, N=32, n_cal=2, cal_rows=16, ln=False, relu=True),
     "one_row": dict(seed=20, d=512, M=1, g=4, bits=3, N=64),
+    # the depth of the large workloads on the 64-token tile (two row tiles, the second ragged; two
+    # column tiles): the int32 accumulators run over all of K without being cleared, so the
+    # literal per-cluster integers are pinned at K = 12288 (3 bit) and K = 20480 (4 bit)
+    "deep_a3": dict(seed=21, d=12288, M=72, g=32, bits=3, N=512, n_cal=2, cal_rows=64),
+    "deep_relu_a4": dict(seed=22, d=20480, M=72, g=32, bits=4, N=512, n_cal=2, cal_rows=64, ln=False, relu=True),
 }
 _cache = {}
 
@@ -106,21 +111,20 @@ def test_calibrate_matches_oracle(rp, name):
 def _folded_site(rp, c):
     cal = c.cal
     k_p = rp.rptq_padded_k(cal.cluster_off)
-    perm_dev = dev(cal.perm.astype(np.int32))
     perm_pad = torch.empty(k_p, dtype=torch.int32, device="cuda")
     gpad = torch.empty(k_p, dtype=torch.float32, device="cuda") if c.ln else None
     bpad = torch.empty(k_p, dtype=torch.float32, device="cuda") if c.ln else None
-    rp.rptq_fold_reorder(dev(c.gamma) if c.ln else None, dev(c.beta) if c.ln else None, c.d, perm_dev, cal.perm,
+    rp.rptq_fold_reorder(dev(c.gamma) if c.ln else None, dev(c.beta) if c.ln else None, c.d, cal.perm,
                          cal.cluster_off, None, None, None, 0, c.d, None, perm_pad, gpad, bpad,
                          None, None, None, None, None)
-    return k_p, perm_dev, perm_pad, gpad, bpad
+    return k_p, perm_pad, gpad, bpad
 
 
 @pytest.mark.parametrize("name", ALL)
 def test_ln_quant_codes_bit_exact(rp, name):
     c = get_case(name)
     cal = c.cal
-    k_p, perm_dev, perm_pad, gpad, bpad = _folded_site(rp, c)
+    k_p, perm_pad, gpad, bpad = _folded_site(rp, c)
     pad_off, k_p_ref = packfmt.padded_layout(cal.cluster_off)
     assert k_p == k_p_ref
     # folded LayerNorm parameters: gamma' = gamma[S], beta' = beta[S] in the padded layout
@@ -164,14 +168,14 @@ def test_ln_quant_codes_bit_exact(rp, name):
 
 def _folded_linear(rp, c, w_dtype=torch.float32):
     cal = c.cal
-    k_p, perm_dev, perm_pad, _, _ = _folded_site(rp, c)
+    k_p, perm_pad, _, _ = _folded_site(rp, c)
     N = c.N
     Wq = torch.zeros(rp.rptq_weight_bytes(N, k_p), dtype=torch.uint8, device="cuda")
     sW = torch.empty(N, dtype=torch.float32, device="cuda")
     zW = torch.empty(N, dtype=torch.int32, device="cuda")
     wsum = torch.empty((N, cal.g_eff), dtype=torch.int32, device="cuda")
     colterm = torch.empty(N, dtype=torch.float32, device="cuda")
-    rp.rptq_fold_reorder(None, None, c.d, perm_dev, cal.perm, cal.cluster_off, cal.s, cal.z,
+    rp.rptq_fold_reorder(None, None, c.d, cal.perm, cal.cluster_off, cal.s, cal.z,
                          dev(c.W, w_dtype), N, c.d, None, perm_pad, None, None, Wq, sW, zW, wsum, colterm)
     torch.cuda.synchronize()
     return k_p, Wq, sW, zW, wsum, colterm
@@ -275,7 +279,7 @@ def test_bf16_weights_accepted(rp):
 def test_empty_batch_is_a_no_op(rp):
     c = get_case("tiny_a4")
     cal = c.cal
-    k_p, perm_dev, perm_pad, gpad, bpad = _folded_site(rp, c)
+    k_p, perm_pad, gpad, bpad = _folded_site(rp, c)
     x = torch.zeros((1, c.d), dtype=torch.bfloat16, device="cuda")        # M = 0 rows of a valid buffer
     codes = torch.full((16,), 7, dtype=torch.uint8, device="cuda")
     rp.rptq_ln_quant(x, 0, c.d, gpad, bpad, EPS, False, perm_pad, cal.cluster_off, cal.s, cal.inv_s, cal.z,

@@ -87,9 +87,60 @@ def test_validation_happens_before_any_device_work(lib):
     assert rp.rptq_cluster_gemm_quant_workspace_bytes(100, 256) == 2 * 100 * 8
     perm = (i32 * 4)(0, 1, 1, 3)
     off4 = (i32 * 2)(0, 4)
-    assert lib.rptq_fold_reorder(None, None, 4, dummy, perm, off4, 1, None, None, None, 0, 0, 4, None,
+    assert lib.rptq_fold_reorder(None, None, 4, perm, off4, 1, None, None, None, 0, 0, 0, 4, None,
                                  dummy, None, None, None, None, None, None, None, None) == -5
     assert b"permutation" in lib.rptq_strerror(-5)
+
+
+def test_fold_reorder_validates_its_index_arrays_on_the_host(lib):
+    """Both index arrays are host arrays: a bad entry is refused before any device work, so an
+    out-of-range source row or channel can never reach a kernel."""
+    i32, vp, f32 = ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
+    dummy = vp(4096)
+    K, N, rows = 64, 8, 8
+    off = (i32 * 2)(0, K)
+    sx, zx = (f32 * 1)(0.5), (i32 * 1)(3)
+    ident = (i32 * K)(*range(K))
+
+    def fold(perm_in=ident, perm_out=None, n=N, w_rows=rows, sx=sx, zx=zx, W=dummy, w_dtype=1):
+        return lib.rptq_fold_reorder(None, None, K, perm_in, off, 1, sx, zx, W, w_dtype, w_rows, n, K, perm_out,
+                                     dummy, None, None, dummy, dummy, dummy, dummy, dummy, None)
+    bad = list(range(K)); bad[5] = K
+    assert fold(perm_in=(i32 * K)(*bad)) == -5                      # channel index out of range
+    bad[5] = -1
+    assert fold(perm_in=(i32 * K)(*bad)) == -5
+    bad[5] = 6
+    assert fold(perm_in=(i32 * K)(*bad)) == -5                      # a channel twice
+    assert fold(perm_out=(i32 * N)(0, 1, 2, 3, 4, 5, rows, 0)) == -5    # source row beyond W
+    assert fold(perm_out=(i32 * N)(0, 1, 2, 3, 4, 5, -2, 0)) == -5      # only -1 marks a pad row
+    assert fold(n=N + 1, w_rows=rows, perm_out=None) == -2              # no output index: N rows of W must exist
+    assert fold(w_rows=0) == -2
+    assert fold(w_dtype=7) == -2
+    assert fold(sx=(f32 * 1)(float("nan"))) == -6
+    assert fold(zx=(i32 * 1)(1 << 22)) == -6
+    assert fold(perm_in=None) == -1
+    # a misaligned device pointer is the first thing checked after the host arrays
+    assert lib.rptq_fold_reorder(None, None, K, ident, off, 1, sx, zx, vp(4100), 1, rows, N, K, None,
+                                 dummy, None, None, dummy, dummy, dummy, dummy, dummy, None) == -4
+
+
+def test_accumulator_headroom_bound_is_declared_and_enforced(lib):
+    """The product kernels never clear their int32 accumulators: |sum| <= 2^14 * K_p.  The header
+    states the bound K_p <= RPTQ_MAX_K_PADDED and every cluster table is checked against it."""
+    header = open(os.path.join(ROOT, "include", "rptq.h")).read()
+    max_kp = int(re.search(r"#define RPTQ_MAX_K_PADDED (\d+)", header).group(1))
+    max_ch = int(re.search(r"#define RPTQ_MAX_CHANNELS (\d+)", header).group(1))
+    max_g = int(re.search(r"#define RPTQ_MAX_CLUSTERS (\d+)", header).group(1))
+    assert (1 << 14) * max_kp <= 1 << 30
+    # the widest table the other limits admit still fits
+    worst = max_ch + max_g * 31
+    assert (worst + 255) // 256 * 256 <= max_kp
+    off = np.concatenate([[0], np.arange(1, max_g) * 33, [max_ch]]).astype(np.int32)
+    assert rp.rptq_padded_k(off) <= max_kp
+    with pytest.raises(rp.RptqError) as e:
+        rp.rptq_padded_k([0, max_ch + 1])
+    assert e.value.status == -2
+    assert b"capture" in lib.rptq_strerror(-9)
 
 
 @pytest.mark.parametrize("cfg,g,bits,seed", [(0, 8, 8, 1), (0, 16, 4, 2), (0, 32, 3, 3), (0, 1, 4, 0)])
