@@ -69,8 +69,8 @@ extern "C" {
 #define RPTQ_N_ALIGN 256
 #define RPTQ_MAX_CHANNELS 32768
 /* Integer headroom of the product kernels: an int8 MFMA operand byte is code << 5, << 4 or
- * << 0 (|.| <= 128) for activations and code << 4 (|.| <= 128) for weights, and the int32
- * accumulators hold the running sum over the whole of K_p without ever being cleared, so
+ * << 0 (|.| <= 128) for activations and code << 4 (|.| <= 128) for weights, and an int32
+ * accumulator holds the sum over one cluster, which may be all of K_p, so
  * |sum| <= 2^14 * K_p.  K_p <= RPTQ_MAX_K_PADDED keeps that below 2^30; every entry point
  * refuses a cluster table whose K_p is larger (RPTQ_ERR_SHAPE). */
 #define RPTQ_MAX_K_PADDED 65536

@@ -6,8 +6,12 @@
 // 32x32x32 int8 MFMA reads its operand.  Weight codes (4 bit, packed in MFMA-lane order) go
 // global -> registers and are expanded to int8 (code << 4) in registers right before use:
 // they never touch LDS, which would otherwise be the bandwidth limit of this kernel.
-// When the last slice of cluster i has been accumulated, the int32 accumulators hold
-// 2^shift * P_i; they are converted, scaled by sX_i / 2^shift and added to the fp32 result.
+// The int32 accumulators hold 2^shift * P_i of the current cluster only: when the last slice
+// of cluster i has been accumulated they are converted, scaled by sX_i / 2^shift, added to
+// the fp32 result and cleared.  (Letting them run on as sums over clusters 1..i and adding
+// (sX_i - sX_{i+1}) * sum saves the clearing, but the fp32 result then passes through
+// intermediate values sX_{i+1} * sum that can be hundreds of times larger than the result
+// when a late cluster has a large scale: at K = 20480 that cost three decimal digits.)
 // The zero-point terms of App. A.4 are applied once at the end from per-row and per-column
 // vectors.
 #include <hip/hip_runtime.h>
@@ -171,9 +175,8 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   };
 
   // ---- accumulators -----------------------------------------------------------------------
-  v16i acc[WM][WN];
-  v16i prev[PARTIALS ? WM : 1][PARTIALS ? WN : 1];          // verification mode: running sum at the last boundary
-  float facc[PARTIALS ? 1 : WM][PARTIALS ? 1 : WN][16];
+  v16i acc[WM][WN];                                         // 2^shift * P_i of the cluster being accumulated
+  float facc[PARTIALS ? 1 : WM][PARTIALS ? 1 : WN][16];     // sum over finished clusters of sX_i P_i
 #pragma unroll
   for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -181,7 +184,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         acc[i][j][r] = 0;
-        if (PARTIALS) prev[i][j][r] = 0;
         if (!PARTIALS) facc[i][j][r] = 0.0f;
       }
     }
@@ -253,6 +255,19 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 #pragma unroll
   for (int j = 0; j < WN; ++j) unpack_w(0, 0, j);
 
+  // Clears one tile's accumulators.  (Written as instructions the optimizer cannot see through:
+  // a known zero would be folded into the next MFMA's C operand, which needs a second copy of
+  // every slice body and measured 7 % slower; 8 two-register moves per tile.)
+  auto clear_tile = [&](int i, int j) {
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      unsigned long long zz;
+      asm volatile("v_mov_b64 %0, 0" : "=v"(zz));
+      acc[i][j][r] = static_cast<int>(zz);
+      acc[i][j][r + 1] = static_cast<int>(zz >> 32);
+    }
+  };
+
   auto k_step = [&](int step, auto parity) {
     constexpr int buf = decltype(parity)::value;            // LDS stage / weight set read by this step
     const unsigned char* cA = sA + buf * A_STAGE;
@@ -269,9 +284,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       // that is due - next slice's activation fragments (LDS reads), next slice's weight
       // fragments (register unpack) and a share of the next stage's activation unpack + LDS
       // write - so that the matrix pipe never waits for a burst of other instructions.
-      // The int32 accumulators are never cleared: they hold the running sum C_i over clusters
-      // 1..i, and sum_i sX_i P_i = sum_i (sX_i - sX_{i+1}) C_i (sX_{g+1} = 0), so a cluster
-      // boundary costs one convert and one fma per accumulator and no branch in the MFMA code.
       {
         constexpr int NM = WM * WN;
         // the step's A units are spread evenly over its slices
@@ -315,7 +327,6 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
       const int gs = step * kStepSlices + s + 1;           // slices accumulated so far
       if (gs == next_end) {                                  // cluster ci is complete (uniform branch)
-        const float sc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, tab_scale), ci));
         if (PARTIALS) {
           const int zx = tab.zx[ci], nn = tab.n[ci];
 #pragma unroll
@@ -327,26 +338,29 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
               for (int r = 0; r < 16; ++r) {
                 const int n = n0 + (wn * WN + j) * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
                 if (t < a.M && n < a.N) {
-                  const int p = (acc[i][j][r] - prev[i][j][r]) >> (ActFmt<BITS>::kShift + 4);
+                  const int p = acc[i][j][r] >> (ActFmt<BITS>::kShift + 4);
                   const int zw = a.zW[n];
                   const int v = p - zx * a.wsum[static_cast<int64_t>(n) * tab.g + ci] -
                                 zw * a.xsum[t * tab.g + ci] + nn * zx * zw;
                   a.yq[(static_cast<int64_t>(ci) * a.M + t) * a.N + n] = v;
                 }
-                prev[i][j][r] = acc[i][j][r];
               }
+              clear_tile(i, j);
             }
         } else {
-          // (while this wave works through the 2 x 16 x WM x WN instructions of the rescale it feeds
-          // the matrix pipe nothing: the other wave of the SIMD gets the issue slots first)
+          // (while this wave works through the instructions of the rescale it feeds the matrix
+          // pipe nothing: the other wave of the SIMD gets the issue slots first)
+          const float sc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, tab_scale), ci));
           __builtin_amdgcn_s_setprio(0);
 #pragma unroll
           for (int i = 0; i < WM; ++i)
 #pragma unroll
-            for (int j = 0; j < WN; ++j)
+            for (int j = 0; j < WN; ++j) {
 #pragma unroll
               for (int r = 0; r < 16; ++r)
                 facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
+              clear_tile(i, j);
+            }
           __builtin_amdgcn_s_setprio(2);
         }
         ++ci;
@@ -670,10 +684,8 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
   for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i) {
     const bool in = i < geom.g;
     tab.slice_end[i] = in ? geom.pad_off[i + 1] / kGroup : -1;
-    // difference of consecutive cluster scales (the accumulators hold running sums)
     const double s_here = (in && sX) ? static_cast<double>(sX[i]) : 0.0;
-    const double s_next = (i + 1 < geom.g && sX) ? static_cast<double>(sX[i + 1]) : 0.0;
-    tab.scale[i] = static_cast<float>((s_here - s_next) / static_cast<double>(1 << shift));
+    tab.scale[i] = static_cast<float>(s_here / static_cast<double>(1 << shift));
     tab.zx[i] = (in && zX) ? zX[i] : 0;
     tab.n[i] = in ? geom.off[i + 1] - geom.off[i] : 0;
   }

@@ -33,7 +33,7 @@ struct GemmArgs {
 struct GemmTab {
   int32_t g;
   int32_t slice_end[RPTQ_MAX_CLUSTERS];   // first slice after cluster i
-  float scale[RPTQ_MAX_CLUSTERS];         // (sX_i - sX_{i+1}) / 2^shift
+  float scale[RPTQ_MAX_CLUSTERS];         // sX_i / 2^shift (the operand bytes are code << shift)
   int32_t zx[RPTQ_MAX_CLUSTERS];
   int32_t n[RPTQ_MAX_CLUSTERS];           // channels in cluster i
 };
