@@ -247,6 +247,27 @@ int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bit
                                 void* next_codes, float* next_rowterm,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- the same call for callers that cannot allocate ------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:
+ * rptq_cluster_gemm_quant without the workspace argument.  The per-column-tile row sums go
+ * to a scratch array of RPTQ_STATIC_SCRATCH_BYTES that lives in the library's device image
+ * (one copy per device, held until the process ends); the call itself allocates nothing.
+ * RPTQ_ERR_WORKSPACE when rptq_cluster_gemm_quant_workspace_bytes(M, N) exceeds that size
+ * (nothing is launched).  Every call on a device uses that device's one array: calls that
+ * overlap in time on one device (two streams, two threads) race on it and must be serialized
+ * by the caller; nothing has to be cleared between calls, every entry that is read was
+ * written by the same call.  As with every launch shape, the first call on a device looks
+ * things up in the driver (here also the array's address) and belongs outside stream capture.
+ * Arguments, results and errors otherwise exactly as rptq_cluster_gemm_quant. */
+#define RPTQ_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t rptq_cluster_gemm_quant_static(const void* codes_packed, int64_t M, int32_t bits,
+                                       const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                       const float* sX, const float* sW, const int32_t* zW,
+                                       const float* colterm, const float* rowterm, int32_t relu,
+                                       const int32_t* next_cluster_off, int32_t next_g, const float* next_s,
+                                       const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
+                                       void* next_codes, float* next_rowterm, void* stream);
+
 /* ---- helpers for verification (not on the timed path) ---------------------------- */
 
 /* The literal per-cluster integers Yq_i of App. A.4 from the same MFMA main loop:

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     rptq_cluster_gemm,
     rptq_cluster_gemm_quant,
     rptq_cluster_gemm_quant_workspace_bytes,
+    rptq_cluster_gemm_quant_static,
     rptq_cluster_gemm_partials,
     rptq_unpack_codes,
     rptq_unpack_weights,

@@ -17,7 +17,7 @@ DTYPE_F32 = 1
 EXPORTED_SYMBOLS = (
     "rptq_padded_k", "rptq_codes_bytes", "rptq_weight_bytes", "rptq_calibrate_workspace_bytes",
     "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_cluster_gemm",
-    "rptq_cluster_gemm_quant", "rptq_cluster_gemm_quant_workspace_bytes",
+    "rptq_cluster_gemm_quant", "rptq_cluster_gemm_quant_workspace_bytes", "rptq_cluster_gemm_quant_static",
     "rptq_cluster_gemm_partials", "rptq_unpack_codes", "rptq_unpack_weights", "rptq_channel_minmax",
     "rptq_cluster_channels", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
 )
@@ -67,6 +67,8 @@ def load_library():
         "rptq_cluster_gemm": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, vp]),
         "rptq_cluster_gemm_quant": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, i32,
                                           vp, i32, vp, vp, vp, i32, vp, vp, vp, sz, vp]),
+        "rptq_cluster_gemm_quant_static": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, i32,
+                                                 vp, i32, vp, vp, vp, i32, vp, vp, vp]),
         "rptq_cluster_gemm_quant_workspace_bytes": (sz, [i64, i32]),
         "rptq_cluster_gemm_partials": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp]),
         "rptq_unpack_codes": (i32, [vp, i64, vp, i32, i32, vp, vp]),
@@ -318,6 +320,24 @@ def rptq_cluster_gemm_quant(codes_packed, M: int, bits: int, Wq_packed, N: int, 
         _dev(next_codes), _dev(next_rowterm, torch.float32), _dev(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "rptq_cluster_gemm_quant")
+
+
+def rptq_cluster_gemm_quant_static(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, sX, sW, zW,
+                                   colterm, rowterm, relu: bool, next_cluster_off, next_s, next_inv_s, next_z,
+                                   next_bits: int, next_codes, next_rowterm, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    sx, psx = _host(sX, np.float32)
+    noff, pnoff = _host(next_cluster_off, np.int32)
+    ns, pns = _host(next_s, np.float32)
+    ni, pni = _host(next_inv_s, np.float32)
+    nz, pnz = _host(next_z, np.int32)
+    st = load_library().rptq_cluster_gemm_quant_static(
+        _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, psx,
+        _dev(sW, torch.float32), _dev(zW, torch.int32), _dev(colterm, torch.float32),
+        _dev(rowterm, torch.float32), int(bool(relu)), pnoff, len(noff) - 1, pns, pni, pnz, next_bits,
+        _dev(next_codes), _dev(next_rowterm, torch.float32), _stream(stream))
+    _check(st, "rptq_cluster_gemm_quant_static")
 
 
 def rptq_cluster_gemm_partials(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, zX, zW, xsum,

@@ -176,16 +176,17 @@ size_t rptq_cluster_gemm_quant_workspace_bytes(int64_t M, int32_t N) {
   return gemm_quant_workspace_bytes(M, N);
 }
 
-int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bits,
+static int32_t gemm_quant_impl(const void* codes_packed, int64_t M, int32_t bits,
                                 const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
                                 const float* sX, const float* sW, const int32_t* zW,
                                 const float* colterm, const float* rowterm, int32_t relu,
                                 const int32_t* next_cluster_off, int32_t next_g, const float* next_s,
                                 const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
                                 void* next_codes, float* next_rowterm,
-                                void* workspace, size_t workspace_bytes, void* stream) {
+                                void* workspace, size_t workspace_bytes, bool static_scratch, void* stream) {
   if (!codes_packed || !Wq_packed || !sX || !sW || !zW || !colterm || !rowterm) return RPTQ_ERR_NULL;
-  if (!next_s || !next_inv_s || !next_z || !next_codes || !next_rowterm || !workspace) return RPTQ_ERR_NULL;
+  if (!next_s || !next_inv_s || !next_z || !next_codes || !next_rowterm) return RPTQ_ERR_NULL;
+  if (!static_scratch && !workspace) return RPTQ_ERR_NULL;
   if (int32_t st = check_bits(bits)) return st;
   if (int32_t st = check_bits(next_bits)) return st;
   ClusterGeom geom, next;
@@ -198,6 +199,9 @@ int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bit
   QuantTab qt;
   if (int32_t st = make_quant_tab(next, next_s, next_inv_s, next_z, next_bits, &qt)) return st;
   if (workspace_bytes < gemm_quant_workspace_bytes(M, N)) return RPTQ_ERR_WORKSPACE;
+  if (static_scratch) {                            // validation is complete: now the device's own array
+    if (int32_t st = gemm_static_scratch(&workspace)) return st;
+  }
   if (!aligned16(codes_packed) || !aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) || !aligned16(colterm) ||
       !aligned16(rowterm) || !aligned16(next_codes) || !aligned16(next_rowterm) || !aligned16(workspace))
     return RPTQ_ERR_ALIGN;
@@ -218,6 +222,31 @@ int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bit
   return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, sX, sW, zW, colterm, rowterm, nullptr,
                      RPTQ_DTYPE_BF16, nullptr, nullptr, nullptr, nullptr, &qo, next_rowterm,
                      static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_cluster_gemm_quant(const void* codes_packed, int64_t M, int32_t bits,
+                                const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                const float* sX, const float* sW, const int32_t* zW,
+                                const float* colterm, const float* rowterm, int32_t relu,
+                                const int32_t* next_cluster_off, int32_t next_g, const float* next_s,
+                                const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
+                                void* next_codes, float* next_rowterm,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  return gemm_quant_impl(codes_packed, M, bits, Wq_packed, N, cluster_off, g, sX, sW, zW, colterm, rowterm, relu,
+                         next_cluster_off, next_g, next_s, next_inv_s, next_z, next_bits, next_codes, next_rowterm,
+                         workspace, workspace_bytes, false, stream);
+}
+
+int32_t rptq_cluster_gemm_quant_static(const void* codes_packed, int64_t M, int32_t bits,
+                                       const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
+                                       const float* sX, const float* sW, const int32_t* zW,
+                                       const float* colterm, const float* rowterm, int32_t relu,
+                                       const int32_t* next_cluster_off, int32_t next_g, const float* next_s,
+                                       const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
+                                       void* next_codes, float* next_rowterm, void* stream) {
+  return gemm_quant_impl(codes_packed, M, bits, Wq_packed, N, cluster_off, g, sX, sW, zW, colterm, rowterm, relu,
+                         next_cluster_off, next_g, next_s, next_inv_s, next_z, next_bits, next_codes, next_rowterm,
+                         nullptr, RPTQ_STATIC_SCRATCH_BYTES, true, stream);
 }
 
 int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t bits,

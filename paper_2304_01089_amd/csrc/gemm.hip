@@ -649,6 +649,30 @@ static int32_t launch_bits(const GemmArgs& a, const GemmTab& tab, int out_mode, 
   return RPTQ_ERR_BITS;
 }
 
+// ---- scratch for callers that cannot allocate ----------------------------------------------
+// The quantizing output stage leaves per-column-tile row sums for its second kernel.  Callers
+// that can neither allocate that workspace nor keep one around use this array instead: one
+// copy per device, held until the process ends, shared by every call on that device.
+static __device__ __align__(256) unsigned char scratch[RPTQ_STATIC_SCRATCH_BYTES];
+
+// Device address of the current device's copy of the array (looked up once per device).  The
+// array's name is only a host-side handle: kernels are given this address.
+int32_t gemm_static_scratch(void** ptr) {
+  static void* addr[kMaxDevices] = {};
+  int dev = 0;
+  if (int32_t s = current_device(&dev)) return s;
+  if (dev < 0 || dev >= kMaxDevices) return RPTQ_ERR_SHAPE;
+  std::lock_guard<std::mutex> lock(state_mutex());
+  if (addr[dev] == nullptr) {
+    void* p = nullptr;
+    RPTQ_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return hip_fail(hipErrorInvalidSymbol);
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return RPTQ_OK;
+}
+
 // Smallest column tile any launch shape uses: bounds the number of column tiles.
 constexpr int kMinTileN = 128;
 

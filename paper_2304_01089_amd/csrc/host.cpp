@@ -375,7 +375,7 @@ const char* rptq_strerror(int32_t status) {
     case RPTQ_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case RPTQ_ERR_PERM: return "not a permutation, or cluster offsets not strictly increasing from 0";
     case RPTQ_ERR_RANGE: return "zero point or scale outside the exactly representable range";
-    case RPTQ_ERR_WORKSPACE: return "workspace too small";
+    case RPTQ_ERR_WORKSPACE: return "workspace too small (or the call needs more than the static scratch array holds)";
     case RPTQ_ERR_HIP: return "a HIP call failed (see rptq_last_hip_error)";
     case RPTQ_ERR_CAPTURE: return "first launch of this shape on this device must happen outside stream capture";
     default: return "unknown status";

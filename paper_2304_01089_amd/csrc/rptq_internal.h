@@ -105,6 +105,8 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
                     const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
                     const GemmQuantOut* quant_out, float* q_rowterm, hipStream_t st);
 size_t gemm_quant_workspace_bytes(int64_t M, int32_t N);
+// Device address of the library's static scratch array on the current device (gemm.hip).
+int32_t gemm_static_scratch(void** ptr);
 int32_t launch_unpack_codes(const void* codes, int64_t rows, const ClusterGeom& geom, int32_t bits, int8_t* out,
                             hipStream_t st);
 int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st);
