@@ -155,8 +155,13 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     ch_idx[c] = ch_ok[c] ? idx : a.chunks - 1;
     ch_lds[c] = ch_ok[c] ? idx * 16 : a.d * 2;
   }
-  constexpr bool kTwoAhead = NCH <= 2;               // registers permitting, the first two rows are requested at once
-  uint4 nxt[NCH], nx1[kTwoAhead ? NCH : 1];
+  // Two register sets hold input rows on their way from HBM: the row staged in iteration i
+  // (row i+1) was requested two iterations earlier, so that two rows per workgroup are in
+  // flight at any time (with one, the bytes in flight per compute unit bound the kernel at
+  // about 3 TB/s: one row of 24 KB per 2 us of loaded-memory latency).
+  // (with four chunks per thread a second set does not fit the 128 registers: one row in flight)
+  constexpr bool kDeep = NCH <= 2;
+  uint4 nxa[NCH], nxb[kDeep ? NCH : 1];
   auto fetch_row = [&](int k, uint4* dst) {          // k-th row of this workgroup; past the end: a valid row again
     int64_t row = row0 + k * stride;
     if (row >= a.M) row = a.M - 1;
@@ -164,11 +169,10 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
 #pragma unroll
     for (int c = 0; c < NCH; ++c) dst[c] = p[ch_idx[c]];
   };
-  auto load_row = [&](int k) { fetch_row(k, nxt); };
   // the first rows are requested before anything else, so that their latency runs under the
   // loads of the per-thread constants below instead of after them
-  fetch_row(0, nxt);
-  if (kTwoAhead) fetch_row(1, nx1);
+  fetch_row(0, nxa);
+  if (kDeep) fetch_row(1, nxb);
 
   // ---- unit waves: per-thread constants, loaded once -----------------------------------------
   uint32_t src[NUNIT][UC];           // LDS byte offsets of the source channels inside a row buffer
@@ -237,11 +241,11 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   }
 
   // registers -> row buffer, exact fp64 sums of this thread's elements -> partials
-  auto stage_row = [&](unsigned char* rowbuf, int pb) {
+  auto stage_row = [&](const uint4* regs, unsigned char* rowbuf, int pb) {
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      uint4 v = nxt[c];
+      uint4 v = regs[c];
       *reinterpret_cast<uint4*>(rowbuf + ch_lds[c]) = v;
       if (LN) {
         if (!ch_ok[c]) v = make_uint4(0u, 0u, 0u, 0u);       // surplus lane: contributes nothing
@@ -264,18 +268,15 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
 
   // ---- pipelined row loop --------------------------------------------------------------------
   int b_cur = 0, b_next = lds.rowbuf_bytes, b_spare = (a.ring == 3) ? 2 * lds.rowbuf_bytes : 0;
-  stage_row(smem + b_cur, 0);
-  if (kTwoAhead) {
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) nxt[c] = nx1[c];
-  } else {
-    load_row(1);
-  }
+  stage_row(nxa, smem + b_cur, 0);
+  fetch_row(kDeep ? 2 : 1, nxa);
   __syncthreads();                                             // row 0 staged
 
-  for (int i = 0; i < n_rows; ++i) {
-    stage_row(smem + b_next, (i + 1) & 1);
-    load_row(i + 2);
+  // one iteration: stage row i+1 from `regs`, request the next row they will hold (i+3, or
+  // i+2 with one set), then gather row i
+  auto row_iter = [&](int i, uint4* regs) {
+    stage_row(regs, smem + b_next, (i + 1) & 1);
+    fetch_row(i + (kDeep ? 3 : 2), regs);
     __syncthreads();                                           // row i+1 staged; {mean, 1/std} of row i published
     const unsigned char* rowbuf = smem + b_cur;
     float mu = 0.0f, rstd = 1.0f;
@@ -342,6 +343,16 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     } else {
       const int t = b_cur; b_cur = b_next; b_next = b_spare; b_spare = t;
     }
+  };
+  if (kDeep) {
+    int i = 0;
+    for (; i + 1 < n_rows; i += 2) {                           // row i+1 waits in nxb, row i+2 in nxa
+      row_iter(i, nxb);
+      row_iter(i + 1, nxa);
+    }
+    if (i < n_rows) row_iter(i, nxb);
+  } else {
+    for (int i = 0; i < n_rows; ++i) row_iter(i, nxa);
   }
   __syncthreads();                                             // last row's partial sums are in LDS
 }
