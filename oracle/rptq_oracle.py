@@ -33,6 +33,16 @@ Parity status of each function (what pins it, in tests/test_oracle_*.py):
 * cluster_gemm_int ................ triple-loop brute force on tiny shapes;
   equality with cluster_gemm_dequant (App. A.4, method 1 == method 2)
                                                               -> pinned
+* kmeans_points ................... equals kmeans bit for bit in two
+  dimensions; brute-force optimal partition of tiny 4-D inputs; pure-Python
+  re-run; Lloyd invariants (partition quality beyond that: parity unpinned,
+  as for kmeans)                                              -> pinned
+* quantize_weights_per_cluster .... Eq. 1-2 written out per (row, cluster);
+  one cluster reduces to quantize_weights                     -> pinned
+* cluster_gemm_int_pc / cluster_gemm_dequant_pc (App. A.4 with its own
+  per-(output, cluster) weight parameters) ... triple loop; method 1 ==
+  method 2; reduces to cluster_gemm_int when every cluster of a row carries
+  the row's pair                                              -> pinned
 """
 from __future__ import annotations
 
@@ -273,6 +283,70 @@ def kmeans(ch_min, ch_max, g: int, seed: int = 0, max_iter: int = 100):
     return labels.astype(np.int64), np.stack([cx, cy], axis=1), n_iter
 
 
+def _sqdist_nd(P, cen):
+    """Squared Euclidean distance of every point [C, D] to one centre [D]:
+    the squares are added in dimension order (separately rounded float64)."""
+    acc = None
+    for j in range(P.shape[-1]):
+        dj = P[..., j] - cen[..., j]
+        sq = dj * dj
+        acc = sq if acc is None else acc + sq
+    return acc
+
+
+def kmeans_points(points, g: int, seed: int = 0, max_iter: int = 100):
+    """The rule of `kmeans` on points of any dimension (used for the points
+    (Qmax, Qmin, Kmax, Kmin) that give queries and keys one shared reorder
+    index, Sec. 4.2): D^2-weighted seeding from SplitMix64(seed), Lloyd
+    iterations until the assignment repeats, ties to the lowest cluster id,
+    member sums in ascending point index, empty clusters re-seeded with the
+    point farthest from its own centre.  Squared distances add their terms in
+    dimension order.  Returns (labels[C], centres[g_used, D], n_iter)."""
+    P = np.asarray(points, dtype=F32).astype(F64)
+    C, D = P.shape
+    if not (1 <= g <= C):
+        raise ValueError("g must be in [1, C]")
+    rng = SplitMix64(seed)
+    first = min(int(rng.uniform() * C), C - 1)
+    cen = [P[first].copy()]
+    d2 = _sqdist_nd(P, cen[0])
+    while len(cen) < g:
+        cum = np.cumsum(d2)
+        total = cum[-1]
+        if not total > 0.0:
+            break
+        target = rng.uniform() * total
+        nxt = min(int(np.searchsorted(cum, target, side="right")), C - 1)
+        cen.append(P[nxt].copy())
+        d2 = np.minimum(d2, _sqdist_nd(P, cen[-1]))
+    gk = len(cen)
+    cen = np.stack(cen, axis=0)
+    labels = np.full(C, -1, dtype=np.int64)
+    n_iter = 0
+    for n_iter in range(1, max_iter + 1):
+        dist = _sqdist_nd(P[:, None, :], cen[None, :, :])            # [C, gk]
+        new_labels = np.argmin(dist, axis=1)
+        if np.array_equal(new_labels, labels):
+            break
+        labels = new_labels
+        cnt = np.bincount(labels, minlength=gk)
+        nz = cnt > 0
+        for j in range(D):
+            sj = np.bincount(labels, weights=P[:, j], minlength=gk)
+            cen[:, j] = np.where(nz, sj / np.maximum(cnt, 1), cen[:, j])
+        if not nz.all():
+            own = _sqdist_nd(P, cen[labels])
+            for kk in np.nonzero(~nz)[0]:
+                far = int(np.argmax(own))
+                cen[kk] = P[far]
+                own[far] = -1.0
+            labels = np.full(C, -1, dtype=np.int64)
+    if (labels < 0).any():
+        dist = _sqdist_nd(P[:, None, :], cen[None, :, :])
+        labels = np.argmin(dist, axis=1)
+    return labels.astype(np.int64), cen, n_iter
+
+
 def canonical_labels(labels):
     """Relabel clusters by first occurrence: the cluster holding channel 0 is 0,
     the next unseen cluster is 1, ...  Empty clusters disappear."""
@@ -375,6 +449,30 @@ def quantize_weights(W, perm_in, perm_out=None, k: int = 4):
     return wq, s, inv_s, z
 
 
+def quantize_weights_per_cluster(W, perm_in, cluster_off, perm_out=None, k: int = 4):
+    """The weight scheme of App. A.4 as printed: W~ = W[perm_out][:, perm_in] is
+    divided along its input channels into the activation's clusters and every
+    (output channel o, cluster i) block gets its own Eq. 2 pair
+    (s^W_{o,i}, z^W_{o,i}) from the block's minimum and maximum, then Eq. 1.
+    Returns (wq int32 [N,K], sW fp32 [N,g], inv_sW fp32 [N,g], zW int64 [N,g])."""
+    W = np.asarray(W, dtype=F32)
+    if perm_out is not None:
+        W = W[perm_out]
+    Wt = W[:, perm_in]
+    g = len(cluster_off) - 1
+    N = Wt.shape[0]
+    wq = np.empty(Wt.shape, dtype=np.int32)
+    sW = np.empty((N, g), dtype=F32)
+    inv = np.empty((N, g), dtype=F32)
+    zW = np.empty((N, g), dtype=np.int64)
+    for i in range(g):
+        a, b = int(cluster_off[i]), int(cluster_off[i + 1])
+        blk = Wt[:, a:b]
+        sW[:, i], inv[:, i], zW[:, i] = minmax_params(blk.min(axis=1), blk.max(axis=1), k)
+        wq[:, a:b] = quantize(blk, inv[:, i][:, None], zW[:, i][:, None], k)
+    return wq, sW, inv, zW
+
+
 # ---------------------------------------------------------------------------
 # Cluster-wise product (App. A.4)
 # ---------------------------------------------------------------------------
@@ -417,3 +515,40 @@ def cluster_gemm_int(xq, wq, cluster_off, sX, zX, sW, zW):
         P[i] = Pi
         Y += float(sX[i]) * np.asarray(sW, dtype=F64)[None, :] * Yq[i].astype(F64)
     return P, Yq, Y
+
+
+def cluster_gemm_dequant_pc(xq, wq, cluster_off, sX, zX, sW, zW):
+    """Method 1 of App. A.4 with per-(output, cluster) weight parameters
+    sW, zW [N, g]: de-quantize every cluster block of both operands, Y = X_hat W_hat^T."""
+    sizes = np.diff(cluster_off)
+    sx_col = np.repeat(np.asarray(sX, dtype=F64), sizes)
+    zx_col = np.repeat(np.asarray(zX, dtype=F64), sizes)
+    xh = sx_col[None, :] * (np.asarray(xq, dtype=F64) - zx_col[None, :])
+    sw_col = np.repeat(np.asarray(sW, dtype=F64), sizes, axis=1)
+    zw_col = np.repeat(np.asarray(zW, dtype=F64), sizes, axis=1)
+    wh = sw_col * (np.asarray(wq, dtype=F64) - zw_col)
+    return xh @ wh.T
+
+
+def cluster_gemm_int_pc(xq, wq, cluster_off, sX, zX, sW, zW):
+    """Method 2 of App. A.4 as printed, with the weight pair of every (output o,
+    cluster i): the integer
+        Yq_i[t,o] = sum_c xq*wq - zX_i sum_c wq[o,c] - zW[o,i] sum_c xq[t,c] + n_i zX_i zW[o,i]
+    and Y = sum_i sX_i sW[o,i] Yq_i.  Returns (Yq int64 [g,M,N], Y float64 [M,N])."""
+    xq = np.asarray(xq)
+    wq = np.asarray(wq)
+    g = len(cluster_off) - 1
+    M, N = xq.shape[0], wq.shape[0]
+    Yq = np.empty((g, M, N), dtype=np.int64)
+    Y = np.zeros((M, N), dtype=F64)
+    zW = np.asarray(zW, dtype=np.int64)
+    sW = np.asarray(sW, dtype=F64)
+    for i in range(g):
+        a, b = int(cluster_off[i]), int(cluster_off[i + 1])
+        Pi = np.rint(xq[:, a:b].astype(F64) @ wq[:, a:b].astype(F64).T).astype(np.int64)
+        wsum = wq[:, a:b].sum(axis=1, dtype=np.int64)
+        xsum = xq[:, a:b].sum(axis=1, dtype=np.int64)
+        zx = int(zX[i])
+        Yq[i] = Pi - zx * wsum[None, :] - zW[None, :, i] * xsum[:, None] + (b - a) * zx * zW[None, :, i]
+        Y += float(sX[i]) * sW[None, :, i] * Yq[i].astype(F64)
+    return Yq, Y

@@ -224,3 +224,109 @@ def test_cluster_params_special_cases():
     s, inv, z, lo, hi = o.cluster_params(cmin, cmax, perm, off, 4)
     sc, invc, zc = o.minmax_params(cmin, cmax, 4)
     assert np.array_equal(s, sc) and np.array_equal(z, zc) and np.array_equal(perm, np.arange(C))
+
+
+# ---------------------------------------------------------------------------
+# kmeans_points: the same rule in any dimension (the shared query/key index, Sec. 4.2)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,C,g", [(0, 40, 4), (1, 97, 8), (2, 64, 16), (4, 50, 1), (5, 33, 33)])
+def test_points_version_equals_the_two_dimensional_one_bit_for_bit(seed, C, g):
+    rng = np.random.default_rng(seed)
+    sc = np.exp(rng.normal(0, 1, C))
+    mid = rng.normal(0, 2 * sc)
+    cmin = (mid - 3 * sc).astype(np.float32)
+    cmax = (mid + 3 * sc).astype(np.float32)
+    raw, cen, n_it = o.kmeans(cmin, cmax, g, seed=seed)
+    raw2, cen2, n_it2 = o.kmeans_points(np.stack([cmin, cmax], axis=1), g, seed=seed)
+    assert np.array_equal(raw, raw2) and np.array_equal(cen, cen2) and n_it == n_it2
+
+
+def _sse_nd(P, labels):
+    return sum((((P[labels == l] - P[labels == l].mean(axis=0)) ** 2).sum()) for l in set(labels.tolist()))
+
+
+@pytest.mark.parametrize("seed", range(5))
+@pytest.mark.parametrize("g", [2, 3])
+def test_points_version_matches_brute_force_in_four_dimensions(seed, g):
+    rng = np.random.default_rng(300 + seed)
+    centres = np.array([[-50.0, -60.0, 5.0, -4.0], [0.0, -5.0, 40.0, 20.0], [60.0, 30.0, -30.0, -45.0]])[:g]
+    sizes = rng.multinomial(8 - g, np.ones(g) / g) + 1
+    pts = np.concatenate([c + rng.normal(0, 0.5, (n, 4)) for c, n in zip(centres, sizes)])
+    pts = pts[rng.permutation(len(pts))].astype(np.float32)
+    raw, cen, _ = o.kmeans_points(pts, g, seed=seed)
+    got, g_eff = o.canonical_labels(raw)
+    P = pts.astype(np.float64)
+    best, best_lab = None, None
+    for lab in itertools.product(range(g), repeat=len(P)):
+        if len(set(lab)) != g:
+            continue
+        lab = np.array(lab)
+        e = _sse_nd(P, lab)
+        if best is None or e < best - 1e-12:
+            best, best_lab = e, lab
+    ref, _ = o.canonical_labels(best_lab)
+    assert g_eff == g and np.array_equal(got, ref)
+
+
+def test_points_version_python_loops_bit_for_bit():
+    """Sequential float64 loops in four dimensions (pins the order of the distance terms and of the member sums)."""
+    rng = np.random.default_rng(77)
+    C, g, seed, D = 60, 5, 11, 4
+    pts = (rng.normal(0, 3, (C, D)) * np.exp(rng.normal(0, 1, (C, 1)))).astype(np.float32)
+    raw, cen, _ = o.kmeans_points(pts, g, seed=seed)
+    P = [[float(v) for v in row] for row in pts]
+    gen = o.SplitMix64(seed)
+
+    def sq(i, c):
+        acc = None
+        for j in range(D):
+            dj = P[i][j] - c[j]
+            t = dj * dj
+            acc = t if acc is None else acc + t
+        return acc
+    first = min(int(gen.uniform() * C), C - 1)
+    cs = [list(P[first])]
+    d2 = [sq(i, cs[0]) for i in range(C)]
+    while len(cs) < g:
+        acc, cum = 0.0, []
+        for v in d2:
+            acc = acc + v
+            cum.append(acc)
+        target = gen.uniform() * cum[-1]
+        nxt = next((i for i in range(C) if cum[i] > target), C - 1)
+        cs.append(list(P[nxt]))
+        d2 = [min(d2[i], sq(i, cs[-1])) for i in range(C)]
+    labels = [-1] * C
+    for _ in range(100):
+        new = []
+        for i in range(C):
+            best, bk = None, 0
+            for kk in range(g):
+                dd = sq(i, cs[kk])
+                if best is None or dd < best:
+                    best, bk = dd, kk
+            new.append(bk)
+        if new == labels:
+            break
+        labels = new
+        for kk in range(g):
+            mem = [i for i in range(C) if labels[i] == kk]
+            assert mem                                           # (no empty cluster on this input)
+            for j in range(D):
+                acc = 0.0
+                for i in mem:
+                    acc = acc + P[i][j]
+                cs[kk][j] = acc / len(mem)
+    assert labels == raw.tolist()
+    assert np.array_equal(np.array(cs), cen)
+
+
+def test_points_version_lloyd_invariants():
+    rng = np.random.default_rng(8)
+    pts = rng.normal(0, 2, (200, 4)).astype(np.float32)
+    raw, cen, n_iter = o.kmeans_points(pts, 6, seed=4)
+    P = pts.astype(np.float64)
+    d = ((P[:, None, :] - cen[None, :, :]) ** 2).sum(axis=2)
+    assert n_iter < 100 and np.array_equal(np.argmin(d, axis=1), raw)
+    for kk in range(6):
+        assert np.allclose(cen[kk], P[raw == kk].mean(axis=0), rtol=1e-12, atol=1e-12)

@@ -160,3 +160,59 @@ def test_quantized_product_approximates_the_float_layer():
         xh = o.dequantize(codes, np.repeat(cal.s, sizes)[None], np.repeat(cal.z, sizes)[None])
         errs.append(np.linalg.norm(xh - y[:, cal.perm]) / np.linalg.norm(y))
     assert errs[1] < 0.5 * errs[0]
+
+
+# ---------------------------------------------------------------------------
+# App. A.4 with its own weight parameters: one (s, z) per (output channel, input cluster)
+# ---------------------------------------------------------------------------
+def test_per_cluster_weight_quantization_is_eq_1_2_on_every_block():
+    s, cal, W = _setup(seed=31, d=40, M=6, g=4, N=7)
+    wq, sW, inv, zW = o.quantize_weights_per_cluster(W, cal.perm, cal.cluster_off)
+    Wt = W[:, cal.perm]
+    for n in range(W.shape[0]):
+        for i in range(cal.g_eff):
+            a, b = cal.cluster_off[i], cal.cluster_off[i + 1]
+            blk = Wt[n, a:b].astype(np.float64)
+            lo, hi = blk.min(), blk.max()
+            if hi == lo:
+                s_ref, z_ref = 1.0, -np.rint(lo)
+            else:
+                s_ref = (hi - lo) / 16.0                              # Eq. 2 with k = 4
+                z_ref = -np.rint((hi + lo) / (2.0 * s_ref))
+            assert float(sW[n, i]) == float(np.float32(s_ref)) and int(zW[n, i]) == int(z_ref)
+            r = (Wt[n, a:b] * inv[n, i]).astype(np.float32).astype(np.float64)
+            assert np.array_equal(wq[n, a:b], np.clip(np.rint(r) + z_ref, -8, 7))
+            # a block's own range is never wider than its row's: the de-quantization error shrinks
+            back = o.dequantize(wq[n, a:b], sW[n, i], zW[n, i])
+            assert np.abs(back - blk).max() <= 2.5 * float(sW[n, i]) + 1e-12
+    # one cluster: the per-row scheme
+    wq1, s1, _, z1 = o.quantize_weights_per_cluster(W, cal.perm, np.array([0, W.shape[1]]))
+    wqr, sr, _, zr = o.quantize_weights(W, cal.perm)
+    assert np.array_equal(wq1, wqr) and np.array_equal(s1[:, 0], sr) and np.array_equal(z1[:, 0], zr)
+
+
+def test_per_cluster_weight_product_both_methods_and_brute_force():
+    s, cal, W = _setup(seed=33, d=36, M=5, g=3, N=6)
+    codes, _, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off, cal.inv_s, cal.z, 4)
+    wq, sW, _, zW = o.quantize_weights_per_cluster(W, cal.perm, cal.cluster_off)
+    Yq, Y = o.cluster_gemm_int_pc(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    Y1 = o.cluster_gemm_dequant_pc(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    assert np.allclose(Y, Y1, rtol=1e-12, atol=1e-12 * np.abs(Y1).max())
+    # triple loop over (token, output, cluster) of the zero-point-corrected integer products
+    for t in range(codes.shape[0]):
+        for n in range(wq.shape[0]):
+            tot = 0.0
+            for i in range(cal.g_eff):
+                a, b = cal.cluster_off[i], cal.cluster_off[i + 1]
+                acc = 0
+                for c in range(a, b):
+                    acc += (int(codes[t, c]) - int(cal.z[i])) * (int(wq[n, c]) - int(zW[n, i]))
+                assert acc == Yq[i, t, n]
+                tot += float(cal.s[i]) * float(sW[n, i]) * acc
+            assert abs(tot - Y[t, n]) <= 1e-12 * max(1.0, abs(tot))
+    # when every cluster of a row carries the row's pair, this is the per-row product
+    wqr, sr, _, zr = o.quantize_weights(W, cal.perm)
+    _, Yq_r, Y_r = o.cluster_gemm_int(codes, wqr, cal.cluster_off, cal.s, cal.z, sr, zr)
+    Yq_b, Y_b = o.cluster_gemm_int_pc(codes, wqr, cal.cluster_off, cal.s, cal.z,
+                                      np.repeat(sr[:, None], cal.g_eff, axis=1), np.repeat(zr[:, None], cal.g_eff, axis=1))
+    assert np.array_equal(Yq_r, Yq_b) and np.allclose(Y_r, Y_b, rtol=1e-13, atol=0)
