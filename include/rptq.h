@@ -268,6 +268,57 @@ int32_t rptq_cluster_gemm_quant_static(const void* codes_packed, int64_t M, int3
                                        const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
                                        void* next_codes, float* next_rowterm, void* stream);
 
+/* ---- attention sites: shared query/key index, key/value cache codes ---------------------
+ * Sec. 4.2 (last paragraph): queries and keys are multiplied over their channels, so they
+ * must share one reorder index; it comes from K-Means over the points
+ * (Qmax_c, Qmin_c, Kmax_c, Kmin_c).  Sec. 5.1: one index per attention head; the settings
+ * W4A4KV, W4A3KV and W3A3KV quantize only the key and value caches.
+ *
+ * rptq_cluster_heads (host only): one clustering per head over the head's d / n_heads
+ * channels, with the K-Means rule of rptq_calibrate on points of two numbers (min, max) for
+ * one tensor, or of four numbers in the order above for two tensors (queries first); head h
+ * is seeded with seed + h.  Channels never leave their head.
+ *   ch_min,ch_max  host arrays of n_tensors (1 or 2) pointers to host fp32 [d]
+ *   assign host int32 [d] out: cluster of each channel inside its head
+ *   perm   host int32 [d] out: reordered position j holds original channel perm[j]
+ *   cluster_off host int32 [n_heads, g+1] out: offsets inside the head; clusters that did not
+ *          form (coinciding points) repeat the last offset;  g_eff host int32 [n_heads] out
+ *   s, inv_s host fp32 [n_tensors, n_heads, g], z host int32 [n_tensors, n_heads, g] out: every
+ *          tensor's own Eq. 2 pair per cluster (1, 1, 0 where the cluster did not form)
+ *
+ * rptq_kv_tables: turns one tensor's part of that result into the device table the two cache
+ * kernels read (one 16-byte entry per position: source channel, 1/s, s, z).  Validates on the
+ * host that perm is a permutation that keeps every channel in its head, that the offsets of
+ * every head run from 0 to d / n_heads without decreasing, and the parameters' ranges.
+ * d % 32 == 0, and d / n_heads must divide 1024 (a wave handles 1024 consecutive channels).
+ * Offline: synchronizes the stream.
+ *   s, inv_s, z    host [n_heads, g]: one tensor's slice of rptq_cluster_heads' output
+ *   table  device out, rptq_kv_table_bytes(d)
+ *
+ * rptq_kv_quant: cache codes of a key or value tensor.  For row t and position j with
+ * source channel c and cluster parameters (s, z):  q = clamp(round(x[t,c] / s) + z, ...)
+ * (Eq. 1, evaluated as in rptq_ln_quant: fp32 product with the stored reciprocal, round half
+ * to even).  The layout is dense: d codes per row in the 32-code group formats above
+ * (d * bits / 8 bytes per row, no cluster padding).
+ *   x device bf16 [T, d] row-major, original channel order;  codes device out [T, d*bits/8]
+ *
+ * rptq_kv_dequant: reads the cache back, x_hat = s (x_q - z) (the line under Eq. 1): the
+ * exact integer difference times the fp32 scale, rounded once to fp32 and then to bf16
+ * (ties to even), in the head's cluster order (the order its consumers - the products with
+ * queries reordered by the same index - work in).
+ *   out device bf16 [T, d]
+ */
+int32_t rptq_cluster_heads(const float* const* ch_min, const float* const* ch_max, int32_t n_tensors, int32_t d,
+                           int32_t n_heads, int32_t g, int32_t bits, uint64_t seed, int32_t max_iter,
+                           int32_t* assign, int32_t* perm, int32_t* cluster_off, float* s, float* inv_s, int32_t* z,
+                           int32_t* g_eff);
+size_t rptq_kv_table_bytes(int32_t d);
+int32_t rptq_kv_tables(const int32_t* perm, const int32_t* cluster_off, const float* s, const float* inv_s,
+                       const int32_t* z, int32_t d, int32_t n_heads, int32_t g, void* table, void* stream);
+int32_t rptq_kv_quant(const void* x, int64_t T, int32_t d, const void* table, int32_t bits, void* codes, void* stream);
+int32_t rptq_kv_dequant(const void* codes, int64_t T, int32_t d, const void* table, int32_t bits, void* out,
+                        void* stream);
+
 /* ---- helpers for verification (not on the timed path) ---------------------------- */
 
 /* The literal per-cluster integers Yq_i of App. A.4 from the same MFMA main loop:

@@ -25,6 +25,11 @@ from .binding import (  # noqa: F401
     rptq_cluster_gemm_partials,
     rptq_unpack_codes,
     rptq_unpack_weights,
+    rptq_cluster_heads,
+    rptq_kv_table_bytes,
+    rptq_kv_tables,
+    rptq_kv_quant,
+    rptq_kv_dequant,
     rptq_device_info,
     rptq_strerror,
     rptq_version,

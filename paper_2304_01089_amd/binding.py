@@ -19,7 +19,8 @@ EXPORTED_SYMBOLS = (
     "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_cluster_gemm",
     "rptq_cluster_gemm_quant", "rptq_cluster_gemm_quant_workspace_bytes", "rptq_cluster_gemm_quant_static",
     "rptq_cluster_gemm_partials", "rptq_unpack_codes", "rptq_unpack_weights", "rptq_channel_minmax",
-    "rptq_cluster_channels", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
+    "rptq_cluster_channels", "rptq_cluster_heads", "rptq_kv_table_bytes", "rptq_kv_tables", "rptq_kv_quant",
+    "rptq_kv_dequant", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
 )
 
 _LIB = None
@@ -75,6 +76,11 @@ def load_library():
         "rptq_unpack_weights": (i32, [vp, i32, vp, i32, vp, vp]),
         "rptq_channel_minmax": (i32, [vp, vp, i32, i32, vp, vp, f32, i32, vp, vp, vp, sz, vp]),
         "rptq_cluster_channels": (i32, [vp, vp, i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_cluster_heads": (i32, [vp, vp, i32, i32, i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_kv_table_bytes": (sz, [i32]),
+        "rptq_kv_tables": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]),
+        "rptq_kv_quant": (i32, [vp, i64, i32, vp, i32, vp, vp]),
+        "rptq_kv_dequant": (i32, [vp, i64, i32, vp, i32, vp, vp]),
         "rptq_device_info": (i32, [vp, vp, vp, vp]),
         "rptq_strerror": (C.c_char_p, [i32]),
         "rptq_last_hip_error": (i32, []),
@@ -349,6 +355,56 @@ def rptq_cluster_gemm_partials(codes_packed, M: int, bits: int, Wq_packed, N: in
         _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, pzx, _dev(zW, torch.int32),
         _dev(xsum, torch.int32), _dev(wsum, torch.int32), _dev(yq, torch.int32), _stream(stream))
     _check(st, "rptq_cluster_gemm_partials")
+
+
+def rptq_cluster_heads(ch_min, ch_max, n_heads: int, g: int, bits: int, seed: int = 0, max_iter: int = 100):
+    """Host-only per-head clustering.  ch_min / ch_max: lists of one (a tensor alone) or two (queries, keys)
+    fp32 arrays [d].  Returns a dict of numpy arrays (see rptq.h)."""
+    mins = [np.ascontiguousarray(a, dtype=np.float32) for a in ch_min]
+    maxs = [np.ascontiguousarray(a, dtype=np.float32) for a in ch_max]
+    nt, d = len(mins), mins[0].shape[0]
+    pmin = (C.c_void_p * nt)(*[a.ctypes.data for a in mins])
+    pmax = (C.c_void_p * nt)(*[a.ctypes.data for a in maxs])
+    assign = np.empty(d, np.int32)
+    perm = np.empty(d, np.int32)
+    off = np.zeros((n_heads, g + 1), np.int32)
+    s = np.zeros((nt, n_heads, g), np.float32)
+    inv_s = np.zeros((nt, n_heads, g), np.float32)
+    z = np.zeros((nt, n_heads, g), np.int32)
+    g_eff = np.zeros(n_heads, np.int32)
+    vp = C.c_void_p
+    st = load_library().rptq_cluster_heads(
+        pmin, pmax, nt, d, n_heads, g, bits, seed, max_iter, assign.ctypes.data_as(vp), perm.ctypes.data_as(vp),
+        off.ctypes.data_as(vp), s.ctypes.data_as(vp), inv_s.ctypes.data_as(vp), z.ctypes.data_as(vp),
+        g_eff.ctypes.data_as(vp))
+    _check(st, "rptq_cluster_heads")
+    return dict(assign=assign, perm=perm, cluster_off=off, s=s, inv_s=inv_s, z=z, g_eff=g_eff)
+
+
+def rptq_kv_table_bytes(d: int) -> int:
+    return int(load_library().rptq_kv_table_bytes(d))
+
+
+def rptq_kv_tables(perm, cluster_off, s, inv_s, z, d: int, n_heads: int, g: int, table, stream=None):
+    pa, pp = _host(perm, np.int32)
+    oa, po = _host(cluster_off, np.int32)
+    sa, ps = _host(s, np.float32)
+    ia, pi = _host(inv_s, np.float32)
+    za, pz = _host(z, np.int32)
+    st = load_library().rptq_kv_tables(pp, po, ps, pi, pz, d, n_heads, g, _dev(table), _stream(stream))
+    _check(st, "rptq_kv_tables")
+
+
+def rptq_kv_quant(x, T: int, d: int, table, bits: int, codes, stream=None):
+    import torch
+    st = load_library().rptq_kv_quant(_dev(x, torch.bfloat16), T, d, _dev(table), bits, _dev(codes), _stream(stream))
+    _check(st, "rptq_kv_quant")
+
+
+def rptq_kv_dequant(codes, T: int, d: int, table, bits: int, out, stream=None):
+    import torch
+    st = load_library().rptq_kv_dequant(_dev(codes), T, d, _dev(table), bits, _dev(out, torch.bfloat16), _stream(stream))
+    _check(st, "rptq_kv_dequant")
 
 
 def rptq_unpack_codes(codes_packed, rows: int, cluster_off, bits: int, out, stream=None):

@@ -249,6 +249,61 @@ int32_t rptq_cluster_gemm_quant_static(const void* codes_packed, int64_t M, int3
                          nullptr, RPTQ_STATIC_SCRATCH_BYTES, true, stream);
 }
 
+size_t rptq_kv_table_bytes(int32_t d) {
+  if (d < 1 || d > RPTQ_MAX_CHANNELS) return 0;
+  return static_cast<size_t>(d) * sizeof(KvPos);
+}
+
+int32_t rptq_kv_tables(const int32_t* perm, const int32_t* cluster_off, const float* s, const float* inv_s,
+                       const int32_t* z, int32_t d, int32_t n_heads, int32_t g, void* table, void* stream) {
+  if (!perm || !cluster_off || !s || !inv_s || !z || !table) return RPTQ_ERR_NULL;
+  if (d < kGroup || d > RPTQ_MAX_CHANNELS || d % kGroup != 0 || n_heads < 1 || d % n_heads != 0) return RPTQ_ERR_SHAPE;
+  const int32_t dh = d / n_heads;
+  if (1024 % dh != 0 || g < 1 || g > dh || g > RPTQ_MAX_CLUSTERS) return RPTQ_ERR_SHAPE;
+  if (int32_t st = check_permutation(perm, d)) return st;
+  std::vector<KvPos> tab(static_cast<size_t>(d));
+  for (int32_t h = 0; h < n_heads; ++h) {
+    const int32_t* off = cluster_off + static_cast<size_t>(h) * (g + 1);
+    if (off[0] != 0 || off[g] != dh) return RPTQ_ERR_PERM;
+    for (int32_t i = 0; i < g; ++i) {
+      if (off[i + 1] < off[i]) return RPTQ_ERR_PERM;
+      if (off[i + 1] == off[i]) continue;
+      const size_t k = static_cast<size_t>(h) * g + i;
+      if (!(std::isfinite(s[k]) && s[k] > 0.0f) || !(std::isfinite(inv_s[k]) && inv_s[k] > 0.0f)) return RPTQ_ERR_RANGE;
+      if (z[k] > kZLimit || z[k] < -kZLimit) return RPTQ_ERR_RANGE;
+      for (int32_t j = off[i]; j < off[i + 1]; ++j) {
+        const int32_t c = perm[h * dh + j];
+        if (c / dh != h) return RPTQ_ERR_PERM;               // a channel may not leave its head
+        tab[h * dh + j] = KvPos{c, inv_s[k], s[k], z[k]};
+      }
+    }
+  }
+  if (!aligned16(table)) return RPTQ_ERR_ALIGN;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  RPTQ_HIP(hipMemcpyAsync(table, tab.data(), tab.size() * sizeof(KvPos), hipMemcpyHostToDevice, hs));
+  RPTQ_HIP(hipStreamSynchronize(hs));
+  return RPTQ_OK;
+}
+
+static int32_t check_kv(const void* a, const void* table, const void* b, int64_t T, int32_t d, int32_t bits) {
+  if (!a || !table || !b) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  if (T < 0 || d < kGroup || d > RPTQ_MAX_CHANNELS || d % kGroup != 0) return RPTQ_ERR_SHAPE;
+  if (!aligned16(a) || !aligned16(table) || !aligned16(b)) return RPTQ_ERR_ALIGN;
+  return RPTQ_OK;
+}
+
+int32_t rptq_kv_quant(const void* x, int64_t T, int32_t d, const void* table, int32_t bits, void* codes, void* stream) {
+  if (int32_t st = check_kv(x, table, codes, T, d, bits)) return st;
+  return launch_kv_quant(x, T, d, static_cast<const KvPos*>(table), bits, codes, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_kv_dequant(const void* codes, int64_t T, int32_t d, const void* table, int32_t bits, void* out,
+                        void* stream) {
+  if (int32_t st = check_kv(codes, table, out, T, d, bits)) return st;
+  return launch_kv_dequant(codes, T, d, static_cast<const KvPos*>(table), bits, out, static_cast<hipStream_t>(stream));
+}
+
 int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t bits,
                                    const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
                                    const int32_t* zX, const int32_t* zW, const int32_t* xsum,

@@ -306,6 +306,171 @@ int32_t cluster_channels(const float* ch_min, const float* ch_max, int32_t d, in
   return RPTQ_OK;
 }
 
+// ---------------------------------------------------------------------------
+// The same K-Means rule on points of any dimension (row-major pts[C][D]): used for the
+// four-number points (Qmax, Qmin, Kmax, Kmin) that give queries and keys one shared reorder
+// index (Sec. 4.2).  Squared distances add their terms in dimension order.
+// ---------------------------------------------------------------------------
+static inline double sqdist_nd(const double* p, const double* c, int D) {
+  double acc = 0.0;
+  for (int j = 0; j < D; ++j) {
+    const double dj = p[j] - c[j];
+    const double sq = dj * dj;
+    acc = (j == 0) ? sq : acc + sq;
+  }
+  return acc;
+}
+
+static void kmeans_nd(const std::vector<double>& pts, size_t C, int D, int32_t g, uint64_t seed, int32_t max_iter,
+                      std::vector<int32_t>& labels, size_t* g_used) {
+  SplitMix64 rng(seed);
+  std::vector<double> cen;                      // [gk][D]
+  std::vector<double> d2(C), cum(C);
+  {
+    size_t first = static_cast<size_t>(rng.uniform() * static_cast<double>(C));
+    first = std::min(first, C - 1);
+    cen.insert(cen.end(), pts.begin() + first * D, pts.begin() + (first + 1) * D);
+    for (size_t i = 0; i < C; ++i) d2[i] = sqdist_nd(&pts[i * D], &cen[0], D);
+  }
+  while (static_cast<int32_t>(cen.size() / D) < g) {
+    double acc = 0.0;
+    for (size_t i = 0; i < C; ++i) {
+      acc = acc + d2[i];
+      cum[i] = acc;
+    }
+    const double total = cum[C - 1];
+    if (!(total > 0.0)) break;
+    const double target = rng.uniform() * total;
+    size_t nxt = std::upper_bound(cum.begin(), cum.end(), target) - cum.begin();
+    nxt = std::min(nxt, C - 1);
+    const size_t k = cen.size() / D;
+    cen.insert(cen.end(), pts.begin() + nxt * D, pts.begin() + (nxt + 1) * D);
+    for (size_t i = 0; i < C; ++i) d2[i] = std::min(d2[i], sqdist_nd(&pts[i * D], &cen[k * D], D));
+  }
+  const size_t gk = cen.size() / D;
+  auto assign_all = [&](std::vector<int32_t>& out) {
+    for (size_t i = 0; i < C; ++i) {
+      double best = sqdist_nd(&pts[i * D], &cen[0], D);
+      int32_t bk = 0;
+      for (size_t k = 1; k < gk; ++k) {
+        const double dd = sqdist_nd(&pts[i * D], &cen[k * D], D);
+        if (dd < best) {
+          best = dd;
+          bk = static_cast<int32_t>(k);
+        }
+      }
+      out[i] = bk;
+    }
+  };
+  labels.assign(C, -1);
+  std::vector<int32_t> fresh(C);
+  std::vector<int64_t> cnt(gk);
+  std::vector<double> sum(gk * D), own(C);
+  for (int it = 0; it < max_iter; ++it) {
+    assign_all(fresh);
+    if (fresh == labels) break;
+    labels = fresh;
+    std::fill(cnt.begin(), cnt.end(), 0);
+    std::fill(sum.begin(), sum.end(), 0.0);
+    for (size_t i = 0; i < C; ++i) {            // ascending point index
+      const int32_t l = labels[i];
+      cnt[l] += 1;
+      for (int j = 0; j < D; ++j) sum[l * D + j] = sum[l * D + j] + pts[i * D + j];
+    }
+    bool any_empty = false;
+    for (size_t k = 0; k < gk; ++k) {
+      if (cnt[k] > 0) {
+        for (int j = 0; j < D; ++j) cen[k * D + j] = sum[k * D + j] / static_cast<double>(cnt[k]);
+      } else {
+        any_empty = true;
+      }
+    }
+    if (any_empty) {
+      for (size_t i = 0; i < C; ++i) own[i] = sqdist_nd(&pts[i * D], &cen[labels[i] * D], D);
+      for (size_t k = 0; k < gk; ++k) {
+        if (cnt[k] > 0) continue;
+        size_t far = 0;
+        for (size_t i = 1; i < C; ++i)
+          if (own[i] > own[far]) far = i;
+        for (int j = 0; j < D; ++j) cen[k * D + j] = pts[far * D + j];
+        own[far] = -1.0;
+      }
+      std::fill(labels.begin(), labels.end(), -1);
+    }
+  }
+  if (std::find(labels.begin(), labels.end(), -1) != labels.end()) assign_all(labels);
+  *g_used = gk;
+}
+
+int32_t cluster_heads(const float* const* ch_min, const float* const* ch_max, int32_t n_tensors, int32_t d,
+                      int32_t n_heads, int32_t g, int32_t bits, uint64_t seed, int32_t max_iter, int32_t* assign,
+                      int32_t* perm, int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff) {
+  if (!ch_min || !ch_max || !assign || !perm || !cluster_off || !s || !inv_s || !z || !g_eff) return RPTQ_ERR_NULL;
+  if (n_tensors != 1 && n_tensors != 2) return RPTQ_ERR_SHAPE;
+  for (int t = 0; t < n_tensors; ++t)
+    if (!ch_min[t] || !ch_max[t]) return RPTQ_ERR_NULL;
+  if (d < 1 || d > RPTQ_MAX_CHANNELS || n_heads < 1 || d % n_heads != 0 || max_iter < 1) return RPTQ_ERR_SHAPE;
+  const int32_t dh = d / n_heads;
+  if (g < 1 || g > dh || g > RPTQ_MAX_CLUSTERS) return RPTQ_ERR_SHAPE;
+  if (int32_t st = check_bits(bits)) return st;
+  for (int t = 0; t < n_tensors; ++t)
+    for (int32_t c = 0; c < d; ++c)
+      if (!std::isfinite(ch_min[t][c]) || !std::isfinite(ch_max[t][c]) || ch_max[t][c] < ch_min[t][c]) return RPTQ_ERR_RANGE;
+  const int D = 2 * n_tensors;
+  std::vector<double> pts(static_cast<size_t>(dh) * D);
+  std::vector<int32_t> labels;
+  for (int32_t h = 0; h < n_heads; ++h) {
+    const int32_t c0 = h * dh;
+    for (int32_t c = 0; c < dh; ++c) {
+      if (n_tensors == 1) {                    // (min, max), as for any single tensor (Sec. 4.1)
+        pts[c * D + 0] = ch_min[0][c0 + c];
+        pts[c * D + 1] = ch_max[0][c0 + c];
+      } else {                                 // (Qmax, Qmin, Kmax, Kmin), as Sec. 4.2 lists them
+        pts[c * D + 0] = ch_max[0][c0 + c];
+        pts[c * D + 1] = ch_min[0][c0 + c];
+        pts[c * D + 2] = ch_max[1][c0 + c];
+        pts[c * D + 3] = ch_min[1][c0 + c];
+      }
+    }
+    size_t gk = 0;
+    kmeans_nd(pts, static_cast<size_t>(dh), D, g, seed + static_cast<uint64_t>(h), max_iter, labels, &gk);
+    // canonical labels by first occurrence, members in ascending channel order
+    std::vector<int32_t> relabel(gk, -1), count;
+    int32_t ge = 0;
+    for (int32_t c = 0; c < dh; ++c) {
+      int32_t& r = relabel[labels[c]];
+      if (r < 0) r = ge++;
+      assign[c0 + c] = r;
+    }
+    count.assign(ge, 0);
+    for (int32_t c = 0; c < dh; ++c) count[assign[c0 + c]] += 1;
+    int32_t* off = cluster_off + static_cast<size_t>(h) * (g + 1);
+    off[0] = 0;
+    for (int32_t k = 0; k < ge; ++k) off[k + 1] = off[k] + count[k];
+    for (int32_t k = ge; k < g; ++k) off[k + 1] = off[ge];
+    std::vector<int32_t> cursor(off, off + ge);
+    for (int32_t c = 0; c < dh; ++c) perm[c0 + cursor[assign[c0 + c]]++] = c0 + c;
+    g_eff[h] = ge;
+    for (int t = 0; t < n_tensors; ++t) {
+      const size_t tb = (static_cast<size_t>(t) * n_heads + h) * g;
+      for (int32_t k = 0; k < g; ++k) {
+        s[tb + k] = 1.0f;
+        inv_s[tb + k] = 1.0f;
+        z[tb + k] = 0;
+      }
+      for (int32_t k = 0; k < ge; ++k) {
+        float lo = ch_min[t][perm[c0 + off[k]]], hi = ch_max[t][perm[c0 + off[k]]];
+        for (int32_t j = off[k]; j < off[k + 1]; ++j) {
+          lo = std::min(lo, ch_min[t][perm[c0 + j]]);
+          hi = std::max(hi, ch_max[t][perm[c0 + j]]);
+        }
+        if (int32_t st = minmax_params(lo + 0.0f, hi + 0.0f, bits, &s[tb + k], &inv_s[tb + k], &z[tb + k])) return st;
+      }
+    }
+  }
+  return RPTQ_OK;
+}
+
 }  // namespace rptq
 
 using namespace rptq;
@@ -340,6 +505,14 @@ int32_t rptq_cluster_channels(const float* ch_min, const float* ch_max, int32_t 
                               uint64_t seed, int32_t max_iter, int32_t* assign, int32_t* perm,
                               int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff) {
   return cluster_channels(ch_min, ch_max, d, g, bits, seed, max_iter, assign, perm, cluster_off, s, inv_s, z, g_eff);
+}
+
+int32_t rptq_cluster_heads(const float* const* ch_min, const float* const* ch_max, int32_t n_tensors, int32_t d,
+                           int32_t n_heads, int32_t g, int32_t bits, uint64_t seed, int32_t max_iter,
+                           int32_t* assign, int32_t* perm, int32_t* cluster_off, float* s, float* inv_s, int32_t* z,
+                           int32_t* g_eff) {
+  return cluster_heads(ch_min, ch_max, n_tensors, d, n_heads, g, bits, seed, max_iter, assign, perm, cluster_off, s,
+                       inv_s, z, g_eff);
 }
 
 int32_t rptq_device_info(int32_t* compute_units, int32_t* clock_khz, int32_t* memory_clock_khz,

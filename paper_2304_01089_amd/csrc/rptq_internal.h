@@ -35,6 +35,15 @@ struct QuantTab {
 
 struct GemmQuantOut;                       // gemm_common.h
 
+// Key/value cache: what the kernels need to know about one position of the per-head cluster
+// order (the cache layout is dense, so every position carries its cluster's constants).
+struct KvPos {
+  int32_t src;                             // original channel held at this position
+  float inv_s;
+  float s;
+  int32_t z;
+};
+
 // Validation helpers (host.cpp).  All return an rptq_status.
 int32_t check_clusters(const int32_t* cluster_off, int32_t g, ClusterGeom* geom);
 int32_t check_bits(int32_t bits);
@@ -110,5 +119,11 @@ int32_t gemm_static_scratch(void** ptr);
 int32_t launch_unpack_codes(const void* codes, int64_t rows, const ClusterGeom& geom, int32_t bits, int8_t* out,
                             hipStream_t st);
 int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st);
+int32_t launch_kv_quant(const void* x, int64_t T, int32_t d, const KvPos* pos, int32_t bits, void* codes, hipStream_t st);
+int32_t launch_kv_dequant(const void* codes, int64_t T, int32_t d, const KvPos* pos, int32_t bits, void* out, hipStream_t st);
+// Per-head clustering (host.cpp), exposed through rptq_cluster_heads.
+int32_t cluster_heads(const float* const* ch_min, const float* const* ch_max, int32_t n_tensors, int32_t d,
+                      int32_t n_heads, int32_t g, int32_t bits, uint64_t seed, int32_t max_iter, int32_t* assign,
+                      int32_t* perm, int32_t* cluster_off, float* s, float* inv_s, int32_t* z, int32_t* g_eff);
 
 }  // namespace rptq

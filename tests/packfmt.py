@@ -42,7 +42,12 @@ def _pack4_groups(c):
 
 def pack_codes(codes, cluster_off, bits):
     """Oracle codes [rows, K] -> packed bytes [rows, K_p*bits/8]."""
-    p = to_padded(codes, cluster_off)
+    return pack_groups(to_padded(codes, cluster_off), bits)
+
+
+def pack_groups(p, bits):
+    """Codes [rows, n] (n a multiple of 32, positions as given) -> the 32-code group formats."""
+    p = np.asarray(p).astype(np.int64)
     rows, k_p = p.shape
     if bits == 8:
         return p.astype(np.int8).view(np.uint8).reshape(rows, k_p)
@@ -65,6 +70,15 @@ def _sext(v, bits):
 def unpack_codes(packed, cluster_off, bits):
     """Packed bytes -> (codes [rows, K] cluster order, pad codes [rows, n_pad])."""
     pad_off, k_p = padded_layout(cluster_off)
+    p = unpack_groups(packed, k_p, bits)
+    mask = np.ones(k_p, dtype=bool)
+    for i in range(len(cluster_off) - 1):
+        mask[pad_off[i]:pad_off[i] + (cluster_off[i + 1] - cluster_off[i])] = False
+    return from_padded(p, cluster_off), p[:, mask]
+
+
+def unpack_groups(packed, k_p, bits):
+    """The 32-code group formats -> codes [rows, k_p]."""
     packed = np.asarray(packed, dtype=np.uint8)
     rows = packed.shape[0]
     if bits == 8:
@@ -85,10 +99,7 @@ def unpack_codes(packed, cluster_off, bits):
             f[..., 24 + b] = ((by[..., b] & 3) << 1) | (by[..., 8 + b] & 1)
             f[..., 28 + b] = ((by[..., 4 + b] & 3) << 1) | ((by[..., 8 + b] >> 1) & 1)
         p = _sext(f, 3).reshape(rows, k_p)
-    mask = np.ones(k_p, dtype=bool)
-    for i in range(len(cluster_off) - 1):
-        mask[pad_off[i]:pad_off[i] + (cluster_off[i + 1] - cluster_off[i])] = False
-    return from_padded(p, cluster_off), p[:, mask]
+    return p
 
 
 def pack_weights(wq, cluster_off):

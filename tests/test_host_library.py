@@ -187,3 +187,49 @@ def test_packed_weight_codec_round_trip():
     assert packed.size == rp.rptq_weight_bytes(70, rp.rptq_padded_k(off))
     back, extra = packfmt.unpack_weights(packed, 70, off)
     assert np.array_equal(back, wq) and (extra == 0).all()
+
+
+def test_head_clustering_matches_oracle_and_tables_are_validated(lib):
+    from oracle import kv_cache as kvo
+    rng = np.random.default_rng(3)
+    H, dh, g, bits = 5, 32, 4, 4
+    d = H * dh
+    qmin = rng.normal(-3, 2, d).astype(np.float32)
+    qmax = (qmin + np.abs(rng.normal(4, 3, d))).astype(np.float32)
+    kmin = rng.normal(-1, 1, d).astype(np.float32)
+    kmax = (kmin + np.abs(rng.normal(2, 1, d))).astype(np.float32)
+    ref = kvo.cluster_heads([qmin, kmin], [qmax, kmax], H, g, bits, 17)
+    got = rp.rptq_cluster_heads([qmin, kmin], [qmax, kmax], H, g, bits, 17)
+    for key in ("assign", "perm", "cluster_off", "g_eff", "s", "inv_s", "z"):
+        assert np.array_equal(got[key], getattr(ref, key)), key
+    ref1 = kvo.cluster_heads([kmin], [kmax], H, g, 3, 2)
+    got1 = rp.rptq_cluster_heads([kmin], [kmax], H, g, 3, 2)
+    for key in ("assign", "perm", "cluster_off", "s", "z"):
+        assert np.array_equal(got1[key], getattr(ref1, key)), key
+    # table construction refuses what the kernels could not survive, before any device work
+    i32, vp, f32 = ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
+    dummy = vp(4096)
+
+    def tables(perm=got["perm"], off=got["cluster_off"], s=got["s"][1], z=got["z"][1], d_=d, heads=H):
+        pa = np.ascontiguousarray(perm, np.int32)
+        oa = np.ascontiguousarray(off, np.int32)
+        sa = np.ascontiguousarray(s, np.float32)
+        za = np.ascontiguousarray(z, np.int32)
+        return lib.rptq_kv_tables(pa.ctypes.data_as(vp), oa.ctypes.data_as(vp), sa.ctypes.data_as(vp),
+                                  sa.ctypes.data_as(vp), za.ctypes.data_as(vp), d_, heads, g, dummy, None)
+    bad = got["perm"].copy()
+    bad[0], bad[dh] = bad[dh], bad[0]                          # two channels swap heads
+    assert tables(perm=bad) == -5
+    bad = got["perm"].copy()
+    bad[3] = bad[4]
+    assert tables(perm=bad) == -5                              # not a permutation
+    off = got["cluster_off"].copy()
+    off[2, g] = dh - 1
+    assert tables(off=off) == -5                               # a head's offsets must end at its width
+    sb = got["s"][1].copy()
+    sb[0, 0] = np.nan
+    assert tables(s=sb) == -6
+    assert tables(d_=d + 8) == -2
+    assert lib.rptq_kv_quant(dummy, 4, d, dummy, 5, dummy, None) == -3
+    assert lib.rptq_kv_dequant(dummy, 4, d + 8, dummy, 4, dummy, None) == -2
+    assert lib.rptq_kv_quant(None, 4, d, dummy, 4, dummy, None) == -1
