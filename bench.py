@@ -304,6 +304,41 @@ def main():
                          ms_max=round(float(np.max(stage_ms[k])), 5), bound=si["bound"], achieved=round(ach, 3),
                          unit=si["unit"], frac=round(ach / si["peak"], 4))
 
+    # ---- rows beyond the step: key/value-cache codes (Sec. 5.1 settings W4A4KV / W4A3KV / W3A3KV) ----------
+    # The first site's input stands in for a key tensor of the layer's width (heads of 128 channels, 4
+    # clusters per head as in Sec. 5.3's ablation outcome); not part of ms_per_step.
+    next_rows = {}
+    d0 = sites[0]["spec"].d
+    if sites[0]["xs"] is not None and d0 % 128 == 0:
+        H = d0 // 128
+        xk = sites[0]["xs"][0]
+        kmin = xk.float().amin(dim=0).cpu().numpy() + np.float32(0)
+        kmax = xk.float().amax(dim=0).cpu().numpy() + np.float32(0)
+        hc = rp.rptq_cluster_heads([kmin], [kmax], H, 4, bits, seed=1)
+        table = torch.empty(rp.rptq_kv_table_bytes(d0), dtype=torch.uint8, device="cuda")
+        rp.rptq_kv_tables(hc["perm"], hc["cluster_off"], hc["s"][0], hc["inv_s"][0], hc["z"][0], d0, H, 4, table)
+        kcodes = torch.empty(M * d0 * bits // 8, dtype=torch.uint8, device="cuda")
+        kback = torch.empty((M, d0), dtype=torch.bfloat16, device="cuda")
+        kv_bytes = M * (2.0 * d0 + d0 * bits / 8.0)
+        for kname, kfn in (("kv_quant", lambda i: rp.rptq_kv_quant(sites[0]["xs"][i % args.sets], M, d0, table, bits, kcodes)),
+                           ("kv_dequant", lambda i: rp.rptq_kv_dequant(kcodes, M, d0, table, bits, kback))):
+            for i in range(5):
+                kfn(i)
+            torch.cuda.synchronize()
+            ts = []
+            for bi in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(R):
+                    kfn(bi * R + i)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) / R)
+            ms = robust_mean(ts)
+            gbs = kv_bytes / (ms * 1e-3) * 1e-9
+            next_rows[kname] = dict(ms=round(ms, 5), bound="hbm", achieved=round(gbs, 1), unit="GB/s",
+                                    frac=round(gbs / PEAK_HBM_GBS, 4), tokens=M, d=d0, heads=H, bits=bits)
+
     # ---- CPU oracle on the host cores (reported baseline) -----------------------------------------
     cpu = None
     if not args.no_cpu:
@@ -312,11 +347,11 @@ def main():
         if os.environ.get("OMP_NUM_THREADS", "").isdigit():      # numpy's BLAS threads: what the oracle really uses
             cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
         rows = M
-        budget_flops = 4e11                       # keeps the leg to roughly 10-30 s of CPU work
+        budget_flops = 1.2e12                     # keeps the leg to roughly 10-30 s of CPU work
         flops_per_row = sum(2.0 * N * s["spec"].d for s in sites for (_, N) in s["spec"].gemms)
         rows = int(max(16, min(M, budget_flops // flops_per_row)))
-        # the oracle keeps the per-cluster integers [g, rows, N] (int64): bound that array to about 2 GB
-        rows = int(max(16, min(rows, 2e9 // (8 * max(s["spec"].g * N for s in sites for (_, N) in s["spec"].gemms)))))
+        # the oracle keeps the per-cluster integers [g, rows, N] (int64): bound that array to about 8 GB
+        rows = int(max(16, min(rows, 8e9 // (8 * max(s["spec"].g * N for s in sites for (_, N) in s["spec"].gemms)))))
         # offline work, untimed: Eq. 1-2 per output row.  Rows are independent, so the oracle's function is
         # called on row blocks (bounded memory) from a thread pool.
         from concurrent.futures import ThreadPoolExecutor
@@ -369,6 +404,7 @@ def main():
         "roofline": roofline,
         "stages": stages,
         "cpu_baseline": cpu,
+        "next_rows": next_rows,
     }
     print(json.dumps(out))
 

@@ -268,6 +268,46 @@ int32_t rptq_cluster_gemm_quant_static(const void* codes_packed, int64_t M, int3
                                        const float* next_inv_s, const int32_t* next_z, int32_t next_bits,
                                        void* next_codes, float* next_rowterm, void* stream);
 
+/* ---- weights with one parameter pair per (output channel, input cluster) ---------------
+ * App. A.4 as printed: the reordered weight matrix is divided along its input channels into
+ * the activation's clusters and every block W~_{o,i} has its own Eq. 2 pair
+ * (s^W_{o,i}, z^W_{o,i}); the second method then gives
+ *   Y[t,o] = sum_i sX_i sW[o,i] ( P_i[t,o] - zX_i wsum[o,i] - zW[o,i] xsum[t,i] + n_i zX_i zW[o,i] ).
+ * The kernels evaluate it as
+ *   Y = sum_i (sX_i sW[o,i]) P_i  -  colterm[o]  -  sum_i (sW[o,i] zW[o,i]) * rowsums[t,i]
+ * with colterm[o] = sum_i sX_i sW[o,i] zX_i wsum[o,i] and rowsums[t,i] = sX_i (xsum[t,i] - n_i zX_i),
+ * the last sum being a rank-g update of the fp32 tile on the matrix cores.  At most 32 clusters.
+ *
+ * rptq_fold_reorder_cw: rptq_fold_reorder's weight part with the per-block parameters.
+ *   perm_in, cluster_off, sX, zX, W, w_dtype, w_rows, N, K, perm_out, perm_pad, Wq_packed: as there
+ *   sW device fp32 [N,g], zW device int32 [N,g], wsum device int32 [N,g] out
+ *   scale_tab device fp32 out, rptq_cw_scale_bytes(N, g): [g, N_p], sX_i sW[o,i] (N_p = N rounded up to 256)
+ *   cross_tab device fp32 out, rptq_cw_cross_bytes(N, g): [N_p, 32], -sW[o,i] zW[o,i] at column
+ *             (i & 1) * 16 + i / 2 (the operand order of the fp32 MFMA of depth 2)
+ *   colterm   device fp32 [N] out
+ * rptq_cluster_rowsums: rowsums of a batch of packed activation codes (an online step, between
+ *   rptq_ln_quant and the product):  rowsums device fp32 out, rptq_cw_rowsum_bytes(M, g): [M, 32],
+ *   same column order as cross_tab.  cluster_off, sX, zX host.
+ * rptq_cluster_gemm_cw: the product.  rptq_cluster_gemm_partials_cw: the literal integers
+ *   Yq_i [g,M,N] with zW device int32 [N,g].
+ */
+size_t rptq_cw_scale_bytes(int32_t N, int32_t g);
+size_t rptq_cw_cross_bytes(int32_t N, int32_t g);
+size_t rptq_cw_rowsum_bytes(int64_t M, int32_t g);
+int32_t rptq_fold_reorder_cw(const int32_t* perm_in, const int32_t* cluster_off, int32_t g, const float* sX,
+                             const int32_t* zX, const void* W, int32_t w_dtype, int32_t w_rows, int32_t N, int32_t K,
+                             const int32_t* perm_out, int32_t* perm_pad, void* Wq_packed, float* sW, int32_t* zW,
+                             int32_t* wsum, float* scale_tab, float* cross_tab, float* colterm, void* stream);
+int32_t rptq_cluster_rowsums(const void* codes_packed, int64_t M, int32_t bits, const int32_t* cluster_off, int32_t g,
+                             const float* sX, const int32_t* zX, float* rowsums, void* stream);
+int32_t rptq_cluster_gemm_cw(const void* codes_packed, int64_t M, int32_t bits, const void* Wq_packed, int32_t N,
+                             const int32_t* cluster_off, int32_t g, const float* scale_tab, const float* cross_tab,
+                             const float* colterm, const float* rowsums, void* y, int32_t y_dtype, void* stream);
+int32_t rptq_cluster_gemm_partials_cw(const void* codes_packed, int64_t M, int32_t bits, const void* Wq_packed,
+                                      int32_t N, const int32_t* cluster_off, int32_t g, const int32_t* zX,
+                                      const int32_t* zW, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
+                                      void* stream);
+
 /* ---- attention sites: shared query/key index, key/value cache codes ---------------------
  * Sec. 4.2 (last paragraph): queries and keys are multiplied over their channels, so they
  * must share one reorder index; it comes from K-Means over the points

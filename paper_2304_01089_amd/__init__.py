@@ -25,6 +25,13 @@ from .binding import (  # noqa: F401
     rptq_cluster_gemm_partials,
     rptq_unpack_codes,
     rptq_unpack_weights,
+    rptq_cw_scale_bytes,
+    rptq_cw_cross_bytes,
+    rptq_cw_rowsum_bytes,
+    rptq_fold_reorder_cw,
+    rptq_cluster_rowsums,
+    rptq_cluster_gemm_cw,
+    rptq_cluster_gemm_partials_cw,
     rptq_cluster_heads,
     rptq_kv_table_bytes,
     rptq_kv_tables,
@@ -37,4 +44,5 @@ from .binding import (  # noqa: F401
     DTYPE_BF16,
     DTYPE_F32,
 )
-from .layer import Calibration, FoldedLinear, calibrate_site, identity_site, fold_linear, ln_quant, cluster_gemm, cluster_gemm_quant  # noqa: F401
+from .layer import (Calibration, FoldedLinear, FoldedLinearCw, calibrate_site, identity_site, fold_linear, ln_quant,  # noqa: F401
+                    cluster_gemm, cluster_gemm_quant, fold_linear_cw, cluster_rowsums, cluster_gemm_cw)

@@ -19,6 +19,8 @@ EXPORTED_SYMBOLS = (
     "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_cluster_gemm",
     "rptq_cluster_gemm_quant", "rptq_cluster_gemm_quant_workspace_bytes", "rptq_cluster_gemm_quant_static",
     "rptq_cluster_gemm_partials", "rptq_unpack_codes", "rptq_unpack_weights", "rptq_channel_minmax",
+    "rptq_cw_scale_bytes", "rptq_cw_cross_bytes", "rptq_cw_rowsum_bytes", "rptq_fold_reorder_cw", "rptq_cluster_rowsums",
+    "rptq_cluster_gemm_cw", "rptq_cluster_gemm_partials_cw",
     "rptq_cluster_channels", "rptq_cluster_heads", "rptq_kv_table_bytes", "rptq_kv_tables", "rptq_kv_quant",
     "rptq_kv_dequant", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
 )
@@ -76,6 +78,13 @@ def load_library():
         "rptq_unpack_weights": (i32, [vp, i32, vp, i32, vp, vp]),
         "rptq_channel_minmax": (i32, [vp, vp, i32, i32, vp, vp, f32, i32, vp, vp, vp, sz, vp]),
         "rptq_cluster_channels": (i32, [vp, vp, i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_cw_scale_bytes": (sz, [i32, i32]),
+        "rptq_cw_cross_bytes": (sz, [i32, i32]),
+        "rptq_cw_rowsum_bytes": (sz, [i64, i32]),
+        "rptq_fold_reorder_cw": (i32, [vp, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "rptq_cluster_rowsums": (i32, [vp, i64, i32, vp, i32, vp, vp, vp, vp]),
+        "rptq_cluster_gemm_cw": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, i32, vp]),
+        "rptq_cluster_gemm_partials_cw": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp]),
         "rptq_cluster_heads": (i32, [vp, vp, i32, i32, i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, vp, vp]),
         "rptq_kv_table_bytes": (sz, [i32]),
         "rptq_kv_tables": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]),
@@ -355,6 +364,79 @@ def rptq_cluster_gemm_partials(codes_packed, M: int, bits: int, Wq_packed, N: in
         _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, pzx, _dev(zW, torch.int32),
         _dev(xsum, torch.int32), _dev(wsum, torch.int32), _dev(yq, torch.int32), _stream(stream))
     _check(st, "rptq_cluster_gemm_partials")
+
+
+def rptq_cw_scale_bytes(N: int, g: int) -> int:
+    return int(load_library().rptq_cw_scale_bytes(N, g))
+
+
+def rptq_cw_cross_bytes(N: int, g: int) -> int:
+    return int(load_library().rptq_cw_cross_bytes(N, g))
+
+
+def rptq_cw_rowsum_bytes(M: int, g: int) -> int:
+    return int(load_library().rptq_cw_rowsum_bytes(M, g))
+
+
+def rptq_fold_reorder_cw(perm_in, cluster_off, sX, zX, W, N: int, K: int, perm_out, perm_pad, Wq_packed, sW, zW, wsum,
+                         scale_tab, cross_tab, colterm, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    ph, pph = _host(perm_in, np.int32)
+    sx, psx = _host(sX, np.float32)
+    zx, pzx = _host(zX, np.int32)
+    po, ppo = (None, None) if perm_out is None else _host(perm_out, np.int32)
+    if W.dtype == torch.float32:
+        w_dtype = DTYPE_F32
+    elif W.dtype == torch.bfloat16:
+        w_dtype = DTYPE_BF16
+    else:
+        raise ValueError("W must be bf16 or fp32")
+    if W.dim() != 2 or W.shape[1] != K:
+        raise ValueError("W must be [rows, K]")
+    st = load_library().rptq_fold_reorder_cw(
+        pph, poff, len(off) - 1, psx, pzx, _dev(W), w_dtype, W.shape[0], N, K, ppo, _dev(perm_pad, torch.int32),
+        _dev(Wq_packed), _dev(sW, torch.float32), _dev(zW, torch.int32), _dev(wsum, torch.int32),
+        _dev(scale_tab, torch.float32), _dev(cross_tab, torch.float32), _dev(colterm, torch.float32), _stream(stream))
+    _check(st, "rptq_fold_reorder_cw")
+
+
+def rptq_cluster_rowsums(codes_packed, M: int, bits: int, cluster_off, sX, zX, rowsums, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    sx, psx = _host(sX, np.float32)
+    zx, pzx = _host(zX, np.int32)
+    st = load_library().rptq_cluster_rowsums(_dev(codes_packed), M, bits, poff, len(off) - 1, psx, pzx,
+                                             _dev(rowsums, torch.float32), _stream(stream))
+    _check(st, "rptq_cluster_rowsums")
+
+
+def rptq_cluster_gemm_cw(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, scale_tab, cross_tab, colterm,
+                         rowsums, y, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    if y.dtype == torch.float32:
+        y_dtype = DTYPE_F32
+    elif y.dtype == torch.bfloat16:
+        y_dtype = DTYPE_BF16
+    else:
+        raise ValueError("y must be bf16 or fp32")
+    st = load_library().rptq_cluster_gemm_cw(
+        _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, _dev(scale_tab, torch.float32),
+        _dev(cross_tab, torch.float32), _dev(colterm, torch.float32), _dev(rowsums, torch.float32), _dev(y), y_dtype,
+        _stream(stream))
+    _check(st, "rptq_cluster_gemm_cw")
+
+
+def rptq_cluster_gemm_partials_cw(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, zX, zW, xsum, wsum,
+                                  yq, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    zx, pzx = _host(zX, np.int32)
+    st = load_library().rptq_cluster_gemm_partials_cw(
+        _dev(codes_packed), M, bits, _dev(Wq_packed), N, poff, len(off) - 1, pzx, _dev(zW, torch.int32),
+        _dev(xsum, torch.int32), _dev(wsum, torch.int32), _dev(yq, torch.int32), _stream(stream))
+    _check(st, "rptq_cluster_gemm_partials_cw")
 
 
 def rptq_cluster_heads(ch_min, ch_max, n_heads: int, g: int, bits: int, seed: int = 0, max_iter: int = 100):

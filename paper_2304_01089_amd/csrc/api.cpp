@@ -168,7 +168,7 @@ int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
       !aligned16(rowterm) || !aligned16(y))
     return RPTQ_ERR_ALIGN;
   return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, sX, sW, zW, colterm, rowterm, y, y_dtype, nullptr,
-                     nullptr, nullptr, nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 size_t rptq_cluster_gemm_quant_workspace_bytes(int64_t M, int32_t N) {
@@ -220,7 +220,7 @@ static int32_t gemm_quant_impl(const void* codes_packed, int64_t M, int32_t bits
     qo.zb[i] = qt.zb[i];
   }
   return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, sX, sW, zW, colterm, rowterm, nullptr,
-                     RPTQ_DTYPE_BF16, nullptr, nullptr, nullptr, nullptr, &qo, next_rowterm,
+                     RPTQ_DTYPE_BF16, nullptr, nullptr, nullptr, nullptr, &qo, next_rowterm, nullptr,
                      static_cast<hipStream_t>(stream));
 }
 
@@ -319,7 +319,110 @@ int32_t rptq_cluster_gemm_partials(const void* codes_packed, int64_t M, int32_t 
       !aligned16(yq))
     return RPTQ_ERR_ALIGN;
   return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, nullptr, nullptr, zW, nullptr, nullptr, nullptr,
-                     RPTQ_DTYPE_F32, zX, xsum, wsum, yq, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                     RPTQ_DTYPE_F32, zX, xsum, wsum, yq, nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+// ---- weights with one parameter pair per (output channel, input cluster): App. A.4 as printed ----
+constexpr int32_t kCwMaxClusters = 32;       // the per-column scale table of a tile lives in LDS
+
+static size_t n_padded_of(int32_t N) { return (static_cast<size_t>(N) + RPTQ_N_ALIGN - 1) / RPTQ_N_ALIGN * RPTQ_N_ALIGN; }
+
+size_t rptq_cw_scale_bytes(int32_t N, int32_t g) {
+  if (N < 1 || g < 1 || g > kCwMaxClusters) return 0;
+  return n_padded_of(N) * static_cast<size_t>(g) * sizeof(float);
+}
+
+size_t rptq_cw_cross_bytes(int32_t N, int32_t g) {
+  if (N < 1 || g < 1 || g > kCwMaxClusters) return 0;
+  return n_padded_of(N) * 32 * sizeof(float);
+}
+
+size_t rptq_cw_rowsum_bytes(int64_t M, int32_t g) {
+  if (M < 0 || g < 1 || g > kCwMaxClusters) return 0;
+  return static_cast<size_t>(M) * 32 * sizeof(float);
+}
+
+int32_t rptq_fold_reorder_cw(const int32_t* perm_in, const int32_t* cluster_off, int32_t g, const float* sX,
+                             const int32_t* zX, const void* W, int32_t w_dtype, int32_t w_rows, int32_t N, int32_t K,
+                             const int32_t* perm_out, int32_t* perm_pad, void* Wq_packed, float* sW, int32_t* zW,
+                             int32_t* wsum, float* scale_tab, float* cross_tab, float* colterm, void* stream) {
+  if (!perm_in || !perm_pad || !W || !Wq_packed || !sW || !zW || !wsum || !scale_tab || !cross_tab || !colterm || !sX || !zX)
+    return RPTQ_ERR_NULL;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (g > kCwMaxClusters) return RPTQ_ERR_SHAPE;
+  if (K < 1 || geom.k != K || N < 1 || w_rows < 1) return RPTQ_ERR_SHAPE;
+  if (!perm_out && N > w_rows) return RPTQ_ERR_SHAPE;
+  if (w_dtype != RPTQ_DTYPE_BF16 && w_dtype != RPTQ_DTYPE_F32) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i) {
+    if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
+    if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
+  }
+  if (perm_out)
+    for (int32_t o = 0; o < N; ++o)
+      if (perm_out[o] < -1 || perm_out[o] >= w_rows) return RPTQ_ERR_PERM;
+  if (int32_t st = check_permutation(perm_in, K)) return st;
+  if (!aligned16(perm_pad) || !aligned16(W) || !aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) ||
+      !aligned16(wsum) || !aligned16(scale_tab) || !aligned16(cross_tab) || !aligned16(colterm))
+    return RPTQ_ERR_ALIGN;
+  std::vector<int32_t> pad(static_cast<size_t>(geom.k_padded), -1);
+  for (int i = 0; i < g; ++i)
+    for (int32_t j = geom.off[i]; j < geom.off[i + 1]; ++j) pad[geom.pad_off[i] + (j - geom.off[i])] = perm_in[j];
+  return launch_fold_cw(pad.data(), geom, sX, zX, W, w_dtype, N, perm_out, perm_pad, Wq_packed, sW, zW, wsum, scale_tab,
+                        cross_tab, colterm, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_cluster_rowsums(const void* codes_packed, int64_t M, int32_t bits, const int32_t* cluster_off, int32_t g,
+                             const float* sX, const int32_t* zX, float* rowsums, void* stream) {
+  if (!codes_packed || !sX || !zX || !rowsums) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || g > kCwMaxClusters) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i) {
+    if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
+    if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
+  }
+  if (!aligned16(codes_packed) || !aligned16(rowsums)) return RPTQ_ERR_ALIGN;
+  return launch_cluster_rowsums(codes_packed, M, geom, bits, sX, zX, rowsums, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_cluster_gemm_cw(const void* codes_packed, int64_t M, int32_t bits, const void* Wq_packed, int32_t N,
+                             const int32_t* cluster_off, int32_t g, const float* scale_tab, const float* cross_tab,
+                             const float* colterm, const float* rowsums, void* y, int32_t y_dtype, void* stream) {
+  if (!codes_packed || !Wq_packed || !scale_tab || !cross_tab || !colterm || !rowsums || !y) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || N < 1 || g > kCwMaxClusters) return RPTQ_ERR_SHAPE;
+  if (y_dtype != RPTQ_DTYPE_BF16 && y_dtype != RPTQ_DTYPE_F32) return RPTQ_ERR_SHAPE;
+  if (!aligned16(codes_packed) || !aligned16(Wq_packed) || !aligned16(scale_tab) || !aligned16(cross_tab) ||
+      !aligned16(colterm) || !aligned16(rowsums) || !aligned16(y))
+    return RPTQ_ERR_ALIGN;
+  const GemmCw cw = {scale_tab, cross_tab, rowsums};
+  // (the per-row scale, zero point and row term of the per-row scheme are not used: their slots read the column term)
+  return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, nullptr, colterm, reinterpret_cast<const int32_t*>(colterm),
+                     colterm, rowsums, y, y_dtype, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, &cw,
+                     static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_cluster_gemm_partials_cw(const void* codes_packed, int64_t M, int32_t bits, const void* Wq_packed,
+                                      int32_t N, const int32_t* cluster_off, int32_t g, const int32_t* zX,
+                                      const int32_t* zW, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
+                                      void* stream) {
+  if (!codes_packed || !Wq_packed || !zX || !zW || !xsum || !wsum || !yq) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || N < 1 || g > kCwMaxClusters) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i)
+    if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
+  if (!aligned16(codes_packed) || !aligned16(Wq_packed) || !aligned16(zW) || !aligned16(xsum) || !aligned16(wsum) ||
+      !aligned16(yq))
+    return RPTQ_ERR_ALIGN;
+  const GemmCw cw = {nullptr, nullptr, nullptr};
+  return launch_gemm(codes_packed, M, bits, Wq_packed, N, geom, nullptr, nullptr, zW, nullptr, nullptr, nullptr,
+                     RPTQ_DTYPE_F32, zX, xsum, wsum, yq, nullptr, nullptr, &cw, static_cast<hipStream_t>(stream));
 }
 
 int32_t rptq_unpack_codes(const void* codes_packed, int64_t rows, const int32_t* cluster_off, int32_t g,

@@ -51,7 +51,12 @@ __device__ __forceinline__ void unpack3(uint32_t x0, uint32_t x1, uint32_t x2, u
 // OUT: what the output stage writes - kOutBf16 / kOutF32: Y; 3, 4 or 8: the next site's packed
 // codes of that many bits (ReLU optional) and the partial row sums its product needs.
 constexpr int kOutBf16 = 0, kOutF32 = 1;
-template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT>
+// CWISE: the weights carry one (s, z) per (output channel, input cluster), as App. A.4 prints the
+// scheme: the rescale of a finished cluster multiplies every output column by its own
+// sX_i sW[o,i] (a table of the tile's columns in LDS), and the zero-point cross term
+// sum_i sW[o,i] zW[o,i] * sX_i (xsum[t,i] - n_i zX_i) is a rank-g update of the fp32 tile, done
+// on the matrix cores (32x32x2 fp32 MFMA) before the output stage.
+template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT, bool CWISE>
 __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTab tab, GemmQuantOut qo) {
   constexpr bool YF32 = OUT == kOutF32;
   constexpr bool QOUT = OUT >= 2;
@@ -74,6 +79,12 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   float* c_ct = c_sw + BN;                                     // [BN]
   float* c_zw = c_ct + BN;                                     // [BN]
   float* c_rt = c_zw + BN;                                     // [BM]
+  // CWISE: per-cluster scales of the tile's columns, [g][BN].  They are read during the main loop
+  // only, so they live between the pipeline buffers and the vectors above when that gap (which
+  // the output tile reuses afterwards) holds 32 clusters, else behind the vectors.
+  constexpr int kCwBytes = 32 * BN * 4;
+  constexpr bool kCwInGap = kConstOff - 2 * A_STAGE >= kCwBytes;
+  float* c_sc = reinterpret_cast<float*>(smem + (kCwInGap ? 2 * A_STAGE : kConstOff + (3 * BN + BM) * 4));
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -176,7 +187,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
 
   // ---- accumulators -----------------------------------------------------------------------
   v16i acc[WM][WN];                                         // 2^shift * P_i of the cluster being accumulated
-  float facc[PARTIALS ? 1 : WM][PARTIALS ? 1 : WN][16];     // sum over finished clusters of sX_i P_i
+  v16f facc[PARTIALS ? 1 : WM][PARTIALS ? 1 : WN];          // sum over finished clusters of sX_i P_i
 #pragma unroll
   for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -239,6 +250,9 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
     c_ct[tid % BN] = p_ct;
     c_zw[tid % BN] = p_zw;
     c_rt[tid % BM] = p_rt;
+  }
+  if (CWISE && !PARTIALS) {                                 // scale table of this tile's columns (n_padded covers the tile)
+    for (int k = tid; k < tab.g * BN; k += 256) c_sc[k] = a.scale_tab[static_cast<int64_t>(k / BN) * a.n_padded + n0 + (k % BN)] * a.cw_prescale;
   }
   __syncthreads();
   load_a(min(2, last), 0);
@@ -339,7 +353,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
                 const int n = n0 + (wn * WN + j) * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
                 if (t < a.M && n < a.N) {
                   const int p = acc[i][j][r] >> (ActFmt<BITS>::kShift + 4);
-                  const int zw = a.zW[n];
+                  const int zw = CWISE ? a.zW[static_cast<int64_t>(n) * tab.g + ci] : a.zW[n];
                   const int v = p - zx * a.wsum[static_cast<int64_t>(n) * tab.g + ci] -
                                 zw * a.xsum[t * tab.g + ci] + nn * zx * zw;
                   a.yq[(static_cast<int64_t>(ci) * a.M + t) * a.N + n] = v;
@@ -356,9 +370,21 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
           for (int i = 0; i < WM; ++i)
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
+              if (CWISE) {                                   // every output column has its own scale for this cluster
+                const float* scp = c_sc + ci * BN + (wn * WN + j) * 32 + (lane >> 5) * 4;
 #pragma unroll
-              for (int r = 0; r < 16; ++r)
-                facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
+                for (int q4 = 0; q4 < 4; ++q4) {
+                  const float4 s4 = *reinterpret_cast<const float4*>(scp + q4 * 8);
+                  facc[i][j][q4 * 4 + 0] = fmaf(static_cast<float>(acc[i][j][q4 * 4 + 0]), s4.x, facc[i][j][q4 * 4 + 0]);
+                  facc[i][j][q4 * 4 + 1] = fmaf(static_cast<float>(acc[i][j][q4 * 4 + 1]), s4.y, facc[i][j][q4 * 4 + 1]);
+                  facc[i][j][q4 * 4 + 2] = fmaf(static_cast<float>(acc[i][j][q4 * 4 + 2]), s4.z, facc[i][j][q4 * 4 + 2]);
+                  facc[i][j][q4 * 4 + 3] = fmaf(static_cast<float>(acc[i][j][q4 * 4 + 3]), s4.w, facc[i][j][q4 * 4 + 3]);
+                }
+              } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                  facc[i][j][r] = fmaf(static_cast<float>(acc[i][j][r]), sc, facc[i][j][r]);
+              }
               clear_tile(i, j);
             }
           __builtin_amdgcn_s_setprio(2);
@@ -387,6 +413,36 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   }
   if (step < steps) k_step(step, std::integral_constant<int, 0>());
   __builtin_amdgcn_s_setprio(0);                             // the output stage yields to a co-resident main loop
+
+  if (CWISE && !PARTIALS) {
+    // Zero-point cross term, fp32 tile += (-sW zW)[n, i] * rtc[t, i] over the clusters i: per
+    // 32 x 32 block g2/2 MFMAs of depth 2.  Lane l supplies row / column l & 31 and depth index
+    // l >> 5; both tables are stored so that a lane's values for all its MFMAs are contiguous.
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(a.cross_tab), 0, a.n_padded * a.g2 * 4, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(a.rtc) + m0 * a.g2, 0, static_cast<int>(rows_here) * a.g2 * 4, kRsrcFlags);
+    const int half = a.g2 / 2;
+    for (int k0 = 0; k0 < half; k0 += 4) {                   // four depth pairs per 16-byte load
+      u4v av[WN], bv[WM];
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+        av[j] = __builtin_amdgcn_raw_buffer_load_b128(
+            x_rsrc, ((n0 + (wn * WN + j) * 32 + (lane & 31)) * a.g2 + (lane >> 5) * half + k0) * 4, 0, 0);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)                           // (rows past M read 0: their outputs are never stored)
+        bv[i] = __builtin_amdgcn_raw_buffer_load_b128(
+            r_rsrc, (((wm * WM + i) * 32 + (lane & 31)) * a.g2 + (lane >> 5) * half + k0) * 4, 0, 0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+          for (int j = 0; j < WN; ++j)
+            facc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[j][kk]), __uint_as_float(bv[i][kk]),
+                                                              facc[i][j], 0, 0, 0);
+    }
+  }
 
   // ---- zero-point terms, output scale, store ----------------------------------------------------
   // D[n][t]: a lane holds one token (lane & 31) and, per register quad, four consecutive output
@@ -473,7 +529,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
         v[e4 * 4 + 0] = f.x; v[e4 * 4 + 1] = f.y; v[e4 * 4 + 2] = f.z; v[e4 * 4 + 3] = f.w;
       }
 #pragma unroll
-      for (int e = 0; e < CW; ++e) v[e] = sw[e] * ((v[e] - ct[e]) - zw[e] * rt[pass]);
+      for (int e = 0; e < CW; ++e) v[e] = CWISE ? (v[e] - ct[e]) : sw[e] * ((v[e] - ct[e]) - zw[e] * rt[pass]);
       if (QOUT) {
         // The value the next site quantizes is the bf16 the plain output stage would have
         // stored; from there on the arithmetic of the quantize-only kernel (Eq. 1): ReLU,
@@ -602,14 +658,17 @@ __global__ void __launch_bounds__(64) rowterm_reduce_kernel(const double* part, 
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT>
+template <int BITS, int WGM, int WGN, int WM, int WN, bool PARTIALS, int OUT, bool CWISE>
 static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuantOut& qo, float* q_rowterm, hipStream_t st) {
   constexpr int BM = WGM * WM * 32, BN = WGN * WN * 32;
   constexpr size_t pipe = 2 * kStepSlices * (2 * BM * 16 + kSlicePad);
   constexpr size_t stage = PARTIALS ? 0 : static_cast<size_t>(BM) * (BN + 4) * 4;   // fp32 output tile of the workgroup
   constexpr size_t terms = PARTIALS ? 0 : static_cast<size_t>(3 * BN + BM) * 4;     // output-stage vectors of the tile
-  constexpr size_t shmem = (pipe > stage ? pipe : stage) + terms;
-  auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, OUT>;
+  // per-cluster column scales: in the gap between the pipeline buffers and the vectors when it holds them
+  constexpr size_t front = pipe > stage ? pipe : stage;
+  constexpr size_t cw_bytes = (CWISE && !PARTIALS) ? static_cast<size_t>(32) * BN * 4 : 0;
+  constexpr size_t shmem = front + terms + ((front - pipe >= cw_bytes) ? 0 : cw_bytes);
+  auto kern = cluster_gemm_kernel<BITS, WGM, WGN, WM, WN, PARTIALS, OUT, CWISE>;
   static LdsGrant lds_granted;
   if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, &lds_granted, st)) return st_lds;
   GemmArgs b = a;
@@ -626,18 +685,26 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuant
   return RPTQ_OK;
 }
 
-template <int BITS, bool PARTIALS, int OUT>
+template <int BITS, bool PARTIALS, int OUT, bool CWISE = false>
 static int32_t launch_shape(const GemmArgs& a, const GemmTab& tab, const GemmQuantOut& qo, float* q_rowterm, hipStream_t st) {
-  if (a.M <= 32) return launch_cfg<BITS, 1, 4, 1, 1, PARTIALS, OUT>(a, tab, qo, q_rowterm, st);
+  if (a.M <= 32) return launch_cfg<BITS, 1, 4, 1, 1, PARTIALS, OUT, CWISE>(a, tab, qo, q_rowterm, st);
   // 64 x 256 tile; every wave covers all 64 tokens and 64 output channels: each expanded
   // weight fragment feeds two MFMAs and no two waves expand the same weights
-  return launch_cfg<BITS, 1, 4, 2, 2, PARTIALS, OUT>(a, tab, qo, q_rowterm, st);
+  return launch_cfg<BITS, 1, 4, 2, 2, PARTIALS, OUT, CWISE>(a, tab, qo, q_rowterm, st);
 }
 
 // out_mode: -1 partial sums, kOutBf16, kOutF32, or the next site's code bits (3, 4, 8)
 template <int BITS>
 static int32_t launch_bits(const GemmArgs& a, const GemmTab& tab, int out_mode, const GemmQuantOut& qo, float* q_rowterm,
                            hipStream_t st) {
+  if (a.scale_tab != nullptr || a.g2 != 0) {               // one weight pair per (output, cluster)
+    switch (out_mode) {
+      case -1: return launch_shape<BITS, true, kOutF32, true>(a, tab, qo, q_rowterm, st);
+      case kOutF32: return launch_shape<BITS, false, kOutF32, true>(a, tab, qo, q_rowterm, st);
+      case kOutBf16: return launch_shape<BITS, false, kOutBf16, true>(a, tab, qo, q_rowterm, st);
+    }
+    return RPTQ_ERR_BITS;
+  }
   switch (out_mode) {
     case -1: return launch_shape<BITS, true, kOutF32>(a, tab, qo, q_rowterm, st);
     case kOutF32: return launch_shape<BITS, false, kOutF32>(a, tab, qo, q_rowterm, st);
@@ -684,7 +751,7 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
                     const ClusterGeom& geom, const float* sX, const float* sW, const int32_t* zW,
                     const float* colterm, const float* rowterm, void* y, int32_t y_dtype,
                     const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
-                    const GemmQuantOut* quant_out, float* q_rowterm, hipStream_t st) {
+                    const GemmQuantOut* quant_out, float* q_rowterm, const GemmCw* cw, hipStream_t st) {
   if (M == 0) return RPTQ_OK;
   GemmArgs a;
   a.codes = static_cast<const uint8_t*>(codes);
@@ -702,9 +769,15 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
   a.xsum = xsum;
   a.wsum = wsum;
   a.yq = yq;
+  const int shift = (bits == 8 ? 0 : (bits == 4 ? 4 : 5)) + 4;
+  a.scale_tab = cw ? cw->scale_tab : nullptr;
+  a.cross_tab = cw ? cw->cross_tab : nullptr;
+  a.rtc = cw ? cw->rtc : nullptr;
+  a.n_padded = (N + RPTQ_N_ALIGN - 1) / RPTQ_N_ALIGN * RPTQ_N_ALIGN;
+  a.g2 = cw ? (geom.g <= 32 ? 32 : 64) : 0;
+  a.cw_prescale = 1.0f / static_cast<float>(1 << shift);
   GemmTab tab;
   tab.g = geom.g;
-  const int shift = (bits == 8 ? 0 : (bits == 4 ? 4 : 5)) + 4;
   for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i) {
     const bool in = i < geom.g;
     tab.slice_end[i] = in ? geom.pad_off[i + 1] / kGroup : -1;

@@ -9,6 +9,7 @@ namespace rptq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct GemmArgs {
   const uint8_t* codes;      // packed activation codes, row-major
@@ -24,6 +25,13 @@ struct GemmArgs {
   const float* colterm;
   const float* rowterm;
   void* y;
+  // weights with one parameter pair per (output, cluster) (App. A.4 as printed)
+  const float* scale_tab;    // [g, n_padded]: sX_i * sW[o,i]
+  const float* cross_tab;    // [n_padded, g2]: -sW[o,i] * zW[o,i], MFMA operand order
+  const float* rtc;          // [M, g2]: de-quantized row sum of every cluster, MFMA operand order
+  int32_t n_padded;
+  int32_t g2;
+  float cw_prescale;         // 2^-shift: the operand bytes are code << shift
   // verification mode
   const int32_t* xsum;
   const int32_t* wsum;

@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
+#include "pack_formats.h"
 #include "rptq_internal.h"
 
 namespace rptq {
@@ -119,37 +120,6 @@ __global__ void __launch_bounds__(256) kv_quant_kernel(const uint4* x, int64_t T
   }
 }
 
-// 32 packed codes -> 32 signed integers, natural order (the formats of the public header).
-template <int BITS>
-__device__ __forceinline__ void kv_decode_group(const uint32_t* w, int* q) {
-  if constexpr (BITS == 8) {
-#pragma unroll
-    for (int j = 0; j < 32; ++j) q[j] = static_cast<int>(w[j / 4] << (24 - 8 * (j & 3))) >> 24;
-  } else if constexpr (BITS == 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        q[8 * u + b] = static_cast<int>(w[u] << (24 - 8 * b)) >> 28;          // high nibble of byte b
-        q[8 * u + 4 + b] = static_cast<int>(w[u] << (28 - 8 * b)) >> 28;      // low nibble
-      }
-  } else {
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int sh = 24 - 8 * b;
-      q[b] = static_cast<int>(w[0] << sh) >> 29;
-      q[4 + b] = static_cast<int>(w[0] << (sh + 3)) >> 29;
-      q[8 + b] = static_cast<int>(w[1] << sh) >> 29;
-      q[12 + b] = static_cast<int>(w[1] << (sh + 3)) >> 29;
-      q[16 + b] = static_cast<int>(w[2] << sh) >> 29;
-      q[20 + b] = static_cast<int>(w[2] << (sh + 3)) >> 29;
-      const uint32_t t0 = (w[0] >> (8 * b)) & 3u, t1 = (w[1] >> (8 * b)) & 3u, lo = (w[2] >> (8 * b)) & 3u;
-      q[24 + b] = static_cast<int>(((t0 << 1) | (lo & 1u)) << 29) >> 29;
-      q[28 + b] = static_cast<int>(((t1 << 1) | (lo >> 1)) << 29) >> 29;
-    }
-  }
-}
-
 template <int BITS>
 __global__ void __launch_bounds__(128) kv_dequant_kernel(const uint8_t* codes, int64_t T, int32_t d, const KvPos* pos,
                                                          uint16_t* out, int32_t blocks_per_row) {
@@ -181,7 +151,7 @@ __global__ void __launch_bounds__(128) kv_dequant_kernel(const uint8_t* codes, i
       }
     }
     int q[32];
-    kv_decode_group<BITS>(w, q);
+    decode_group<BITS>(w, q);
     uint32_t o[16];
 #pragma unroll
     for (int j = 0; j < 32; j += 2) {

@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
+#include "pack_formats.h"
 #include "rptq_internal.h"
 
 namespace rptq {
@@ -396,6 +397,51 @@ __global__ void xsum_kernel(const uint8_t* codes, int64_t M, int32_t row_bytes, 
   xsum[row * geom.g + i] = acc;
 }
 
+// De-quantized row sum of every cluster, rtc[t, i] = sX_i (sum_{c in i} xq[t,c] - n_i zX_i): what the
+// zero-point cross term of App. A.4 needs per (token, cluster) when the weights carry one
+// zero point per (output, cluster).  One wave per row; a 32-code group lies inside one
+// cluster, so a lane adds whole groups into the cluster's integer sum (exact, order-free).
+// Output position of cluster i in a row of g2 floats: (i & 1) * g2/2 + i/2 (the operand order
+// of the 32x32x2 fp32 MFMA that consumes it).
+struct RowSumTab {
+  double s[RPTQ_MAX_CLUSTERS];
+  double nz[RPTQ_MAX_CLUSTERS];        // n_i * zX_i
+};
+
+template <int BITS>
+__global__ void __launch_bounds__(256) cluster_rowsums_kernel(const uint8_t* codes, int64_t M, int32_t row_bytes,
+                                                              ClusterGeom geom, RowSumTab tab, float* rtc, int32_t g2) {
+  constexpr int GB = BITS * 4;
+  __shared__ int32_t acc[4][RPTQ_MAX_CLUSTERS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+  if (lane < RPTQ_MAX_CLUSTERS) acc[wave][lane] = 0;
+  __builtin_amdgcn_wave_barrier();
+  if (row < M) {
+    const int groups = geom.pad_off[geom.g] / kGroup;
+    for (int gi = lane; gi < groups; gi += kWave) {
+      const uint32_t* p = reinterpret_cast<const uint32_t*>(codes + row * row_bytes + static_cast<int64_t>(gi) * GB);
+      uint32_t w[GB / 4];
+#pragma unroll
+      for (int k = 0; k < GB / 4; ++k) w[k] = p[k];
+      int q[32];
+      decode_group<BITS>(w, q);
+      int sum = 0;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) sum += q[j];
+      int ci = 0;
+      for (int i = 1; i < geom.g; ++i) ci += (gi * kGroup >= geom.pad_off[i]) ? 1 : 0;
+      atomicAdd(&acc[wave][ci], sum);
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (row < M && lane < g2) {
+    float v = 0.0f;
+    if (lane < geom.g) v = static_cast<float>(tab.s[lane] * (static_cast<double>(acc[wave][lane]) - tab.nz[lane]));
+    rtc[row * g2 + (lane & 1) * (g2 / 2) + (lane >> 1)] = v;
+  }
+}
+
 template <int BITS>
 __global__ void unpack_codes_kernel(const uint8_t* codes, int64_t rows, int32_t row_bytes, ClusterGeom geom, int8_t* out) {
   const int64_t row = blockIdx.x;
@@ -531,6 +577,26 @@ int32_t launch_ln_quant(const void* x, int64_t M, int32_t d, const float* gamma_
     else hipLaunchKernelGGL(xsum_kernel<8>, dim3(static_cast<unsigned>(M)), dim3(thr), 0, st, a.codes, M, a.row_bytes, geom, xsum);
     RPTQ_HIP(hipGetLastError());
   }
+  return RPTQ_OK;
+}
+
+int32_t launch_cluster_rowsums(const void* codes, int64_t M, const ClusterGeom& geom, int32_t bits, const float* sX,
+                               const int32_t* zX, float* rtc, hipStream_t st) {
+  if (M == 0) return RPTQ_OK;
+  RowSumTab tab;
+  for (int i = 0; i < RPTQ_MAX_CLUSTERS; ++i) {
+    const bool in = i < geom.g;
+    tab.s[i] = in ? static_cast<double>(sX[i]) : 0.0;
+    tab.nz[i] = in ? static_cast<double>(geom.off[i + 1] - geom.off[i]) * static_cast<double>(zX[i]) : 0.0;
+  }
+  const int g2 = geom.g <= 32 ? 32 : 64;
+  const uint8_t* c = static_cast<const uint8_t*>(codes);
+  const int32_t row_bytes = geom.k_padded * bits / 8;
+  const dim3 grid(static_cast<unsigned>((M + 3) / 4)), block(256);
+  if (bits == 3) hipLaunchKernelGGL(cluster_rowsums_kernel<3>, grid, block, 0, st, c, M, row_bytes, geom, tab, rtc, g2);
+  else if (bits == 4) hipLaunchKernelGGL(cluster_rowsums_kernel<4>, grid, block, 0, st, c, M, row_bytes, geom, tab, rtc, g2);
+  else hipLaunchKernelGGL(cluster_rowsums_kernel<8>, grid, block, 0, st, c, M, row_bytes, geom, tab, rtc, g2);
+  RPTQ_HIP(hipGetLastError());
   return RPTQ_OK;
 }
 

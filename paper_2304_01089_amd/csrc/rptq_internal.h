@@ -35,6 +35,13 @@ struct QuantTab {
 
 struct GemmQuantOut;                       // gemm_common.h
 
+// Tables of a linear layer whose weights carry one (s, z) per (output, cluster) (App. A.4 as printed).
+struct GemmCw {
+  const float* scale_tab;                  // [g, N_p]
+  const float* cross_tab;                  // [N_p, g2]; NULL in verification mode
+  const float* rtc;                        // [M, g2]; NULL in verification mode
+};
+
 // Key/value cache: what the kernels need to know about one position of the per-head cluster
 // order (the cache layout is dense, so every position carries its cluster's constants).
 struct KvPos {
@@ -112,7 +119,13 @@ int32_t launch_gemm(const void* codes, int64_t M, int32_t bits, const void* Wq, 
                     const ClusterGeom& geom, const float* sX, const float* sW, const int32_t* zW,
                     const float* colterm, const float* rowterm, void* y, int32_t y_dtype,
                     const int32_t* zX, const int32_t* xsum, const int32_t* wsum, int32_t* yq,
-                    const GemmQuantOut* quant_out, float* q_rowterm, hipStream_t st);
+                    const GemmQuantOut* quant_out, float* q_rowterm, const GemmCw* cw, hipStream_t st);
+int32_t launch_fold_cw(const int32_t* perm_pad_host, const ClusterGeom& geom, const float* sX, const int32_t* zX,
+                       const void* W, int32_t w_dtype, int32_t N, const int32_t* perm_out_host, int32_t* perm_pad,
+                       void* Wq_packed, float* sW, int32_t* zW, int32_t* wsum, float* scale_tab, float* cross_tab,
+                       float* colterm, hipStream_t st);
+int32_t launch_cluster_rowsums(const void* codes, int64_t M, const ClusterGeom& geom, int32_t bits, const float* sX,
+                               const int32_t* zX, float* rtc, hipStream_t st);
 size_t gemm_quant_workspace_bytes(int64_t M, int32_t N);
 // Device address of the library's static scratch array on the current device (gemm.hip).
 int32_t gemm_static_scratch(void** ptr);

@@ -136,3 +136,51 @@ def cluster_gemm_quant(cal: Calibration, lin: FoldedLinear, codes, rowterm, M, n
                               rowterm, relu, next_site.cluster_off, next_site.s, next_site.inv_s, next_site.z,
                               next_site.bits, next_codes, next_rowterm, workspace)
     return next_codes, next_rowterm
+
+
+# ---- weights with one parameter pair per (output channel, input cluster): App. A.4 as printed ----
+@dataclass
+class FoldedLinearCw:
+    N: int
+    Wq: object
+    sW: object            # [N, g]
+    zW: object            # [N, g]
+    wsum: object          # [N, g]
+    scale_tab: object     # [g, N_p]
+    cross_tab: object     # [N_p, 32]
+    colterm: object       # [N]
+
+
+def fold_linear_cw(cal: Calibration, W, perm_out=None) -> FoldedLinearCw:
+    import torch
+    N, K = (W.shape[0] if perm_out is None else len(perm_out)), W.shape[1]
+    dev, g = W.device, cal.g_eff
+    out = FoldedLinearCw(
+        N=N,
+        Wq=torch.empty(B.rptq_weight_bytes(N, cal.k_padded), dtype=torch.uint8, device=dev),
+        sW=torch.empty((N, g), dtype=torch.float32, device=dev),
+        zW=torch.empty((N, g), dtype=torch.int32, device=dev),
+        wsum=torch.empty((N, g), dtype=torch.int32, device=dev),
+        scale_tab=torch.empty(B.rptq_cw_scale_bytes(N, g) // 4, dtype=torch.float32, device=dev),
+        cross_tab=torch.empty(B.rptq_cw_cross_bytes(N, g) // 4, dtype=torch.float32, device=dev),
+        colterm=torch.empty(N, dtype=torch.float32, device=dev))
+    B.rptq_fold_reorder_cw(cal.perm, cal.cluster_off, cal.s, cal.z, W, N, K, perm_out, cal.perm_pad, out.Wq, out.sW,
+                           out.zW, out.wsum, out.scale_tab, out.cross_tab, out.colterm)
+    return out
+
+
+def cluster_rowsums(cal: Calibration, codes, M, rowsums=None):
+    import torch
+    if rowsums is None:
+        rowsums = torch.empty(max(4, B.rptq_cw_rowsum_bytes(M, cal.g_eff) // 4), dtype=torch.float32, device=codes.device)
+    B.rptq_cluster_rowsums(codes, M, cal.bits, cal.cluster_off, cal.s, cal.z, rowsums)
+    return rowsums
+
+
+def cluster_gemm_cw(cal: Calibration, lin: FoldedLinearCw, codes, rowsums, M, y=None, dtype=None):
+    import torch
+    if y is None:
+        y = torch.empty((M, lin.N), dtype=dtype or torch.bfloat16, device=codes.device)
+    B.rptq_cluster_gemm_cw(codes, M, cal.bits, lin.Wq, lin.N, cal.cluster_off, lin.scale_tab, lin.cross_tab, lin.colterm,
+                           rowsums, y)
+    return y
