@@ -339,6 +339,80 @@ def main():
             next_rows[kname] = dict(ms=round(ms, 5), bound="hbm", achieved=round(gbs, 1), unit="GB/s",
                                     frac=round(gbs / PEAK_HBM_GBS, 4), tokens=M, d=d0, heads=H, bits=bits)
 
+    # ... the reorder fused into LayerNorm the way Sec. 4.2 words it (original channel order, the reorder index
+    # offsets the write address: one int8 per code, then a packing kernel), beside the LDS-gather kernel of the step
+    if sites[0]["xs"] is not None:
+        s0, cal0 = sites[0], sites[0]["cal"]
+        g0, b0 = torch.from_numpy(host_sites[0]["site"].gamma).cuda(), torch.from_numpy(host_sites[0]["site"].beta).cuda()
+        ws0 = torch.empty(rp.rptq_ln_quant_scatter_workspace_bytes(M, d0, cal0.k_padded) + 256, dtype=torch.uint8, device="cuda")
+        ws0 = ws0[(-ws0.data_ptr()) % 256:]
+        codes_sc = torch.empty_like(s0["codes"])
+
+        def sc_fn(i):
+            rp.rptq_ln_quant_scatter(s0["xs"][i % args.sets], M, d0, g0, b0, EPS, False, cal0.perm_pad, cal0.cluster_off,
+                                     cal0.inv_s, cal0.z, bits, codes_sc, ws0)
+        for i in range(3):
+            sc_fn(i)
+        torch.cuda.synchronize()
+        ts = []
+        for bi in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(R):
+                sc_fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / R)
+        ms = robust_mean(ts)
+        gbs = M * (2.0 * d0 + d0 * bits / 8.0) / (ms * 1e-3) * 1e-9
+        next_rows["ln_quant_scatter:%s" % s0["spec"].name] = dict(
+            ms=round(ms, 5), bound="hbm", achieved=round(gbs, 1), unit="GB/s", frac=round(gbs / PEAK_HBM_GBS, 4),
+            gather_kernel_ms=round(stage_avg["ln_quant:%s" % s0["spec"].name], 5))
+        del ws0, codes_sc
+
+    # ... and the product with one weight parameter pair per (output channel, input cluster), App. A.4 as
+    # printed, on the last site's first linear layer (at most 32 clusters): per-cluster row sums + product
+    s_last, hs_last = sites[-1], host_sites[-1]
+    if s_last["cal"].g_eff <= 32 and s_last["lins"][0]["ys"] is not None:
+        cal_l, lin_l = s_last["run_cal"], s_last["lins"][0]
+        Wl = torch.from_numpy(hs_last["W"][0]).cuda()
+        lcw = rp.fold_linear_cw(s_last["cal"], Wl)
+        del Wl
+        rsums = torch.empty(rp.rptq_cw_rowsum_bytes(M, cal_l.g_eff) // 4, dtype=torch.float32, device="cuda")
+        ycw = lin_l["ys"][0]
+        d_l, N_l = s_last["spec"].d, lin_l["N"]
+
+        def cw_sums(i):
+            rp.rptq_cluster_rowsums(s_last["codes"], M, bits, cal_l.cluster_off, cal_l.s, cal_l.z, rsums)
+
+        def cw_gemm(i):
+            rp.rptq_cluster_gemm_cw(s_last["codes"], M, bits, lcw.Wq, lcw.N, cal_l.cluster_off, lcw.scale_tab,
+                                    lcw.cross_tab, lcw.colterm, rsums, ycw)
+        cw_sums(0)
+        for kname, kfn, work, peak, unit, scale, bound in (
+                ("cluster_rowsums:%s" % lin_l["name"], cw_sums, M * d_l * bits / 8.0, PEAK_HBM_GBS, "GB/s", 1e-9, "hbm"),
+                ("gemm_cw:%s" % lin_l["name"], cw_gemm, 2.0 * M * N_l * d_l,
+                 PEAK_HBM_GBS if M <= 32 else PEAK_INT8_TOPS, "GB/s" if M <= 32 else "TOP/s", 1e-9 if M <= 32 else 1e-12,
+                 "hbm" if M <= 32 else "mfma")):
+            if kname.startswith("gemm_cw") and M <= 32:
+                work = N_l * d_l / 2.0 + M * d_l * bits / 8.0 + M * N_l * 2.0
+            for i in range(3):
+                kfn(i)
+            torch.cuda.synchronize()
+            ts = []
+            for bi in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(R):
+                    kfn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) / R)
+            ms = robust_mean(ts)
+            ach = work / (ms * 1e-3) * scale
+            next_rows[kname] = dict(ms=round(ms, 5), bound=bound, achieved=round(ach, 1), unit=unit, frac=round(ach / peak, 4))
+        del lcw
+
     # ---- CPU oracle on the host cores (reported baseline) -----------------------------------------
     cpu = None
     if not args.no_cpu:

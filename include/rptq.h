@@ -200,6 +200,23 @@ int32_t rptq_ln_quant(const void* x, int64_t M, int32_t d,
                       const float* s, const float* inv_s, const int32_t* z, int32_t bits,
                       void* codes_packed, int32_t* xsum, float* rowterm, void* stream);
 
+/* ---- the same stage with the reorder as an offset of the write address ----------------
+ * Sec. 4.2 ("Avoid explicit reordering") as the paper words it: LayerNorm runs in the
+ * original channel order with gamma and beta untouched, and every result is written to the
+ * address its reorder index gives it.  The smallest unit of a scattered write is a byte, so
+ * the codes leave as one int8 each into an [M, K_p] buffer in the workspace and a second
+ * kernel packs them.  Kept as the measured alternative to rptq_ln_quant (which gathers through
+ * LDS and stores packed codes once); the packed codes are bit-identical.  No rowterm / xsum.
+ *  gamma,beta device fp32 [d] in the ORIGINAL channel order (both NULL: no LayerNorm)
+ *  workspace  device, 256-byte aligned, rptq_ln_quant_scatter_workspace_bytes(M, d, K_p)
+ *  other arguments as rptq_ln_quant
+ */
+size_t rptq_ln_quant_scatter_workspace_bytes(int64_t M, int32_t d, int32_t k_padded);
+int32_t rptq_ln_quant_scatter(const void* x, int64_t M, int32_t d, const float* gamma, const float* beta, float eps,
+                              int32_t relu, const int32_t* perm_pad, const int32_t* cluster_off, int32_t g,
+                              const float* inv_s, const int32_t* z, int32_t bits, void* codes_packed,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- online stage 3: cluster-wise integer product (App. A.4, second method) ------
  * Per cluster i the int32 product P_i[t,o] = sum_{c in i} xq[t,c] wq[o,c] runs on int8
  * MFMA; with the zero-point terms of App. A.4 the result is
@@ -289,7 +306,9 @@ int32_t rptq_cluster_gemm_quant_static(const void* codes_packed, int64_t M, int3
  *   rptq_ln_quant and the product):  rowsums device fp32 out, rptq_cw_rowsum_bytes(M, g): [M, 32],
  *   same column order as cross_tab.  cluster_off, sX, zX host.
  * rptq_cluster_gemm_cw: the product.  rptq_cluster_gemm_partials_cw: the literal integers
- *   Yq_i [g,M,N] with zW device int32 [N,g].
+ *   Yq_i [g,M,N] with zW device int32 [N,g] (a weight block that lies far from zero relative to
+ *   its width has a zero point of up to 2^28, which is carried exactly everywhere; the int32
+ *   Yq_i are then stored modulo 2^32).
  */
 size_t rptq_cw_scale_bytes(int32_t N, int32_t g);
 size_t rptq_cw_cross_bytes(int32_t N, int32_t g);

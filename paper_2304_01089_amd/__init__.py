@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     rptq_calibrate,
     rptq_fold_reorder,
     rptq_ln_quant,
+    rptq_ln_quant_scatter,
+    rptq_ln_quant_scatter_workspace_bytes,
     rptq_cluster_gemm,
     rptq_cluster_gemm_quant,
     rptq_cluster_gemm_quant_workspace_bytes,

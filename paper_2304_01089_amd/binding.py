@@ -16,7 +16,8 @@ DTYPE_F32 = 1
 
 EXPORTED_SYMBOLS = (
     "rptq_padded_k", "rptq_codes_bytes", "rptq_weight_bytes", "rptq_calibrate_workspace_bytes",
-    "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_cluster_gemm",
+    "rptq_calibrate", "rptq_fold_reorder", "rptq_ln_quant", "rptq_ln_quant_scatter",
+    "rptq_ln_quant_scatter_workspace_bytes", "rptq_cluster_gemm",
     "rptq_cluster_gemm_quant", "rptq_cluster_gemm_quant_workspace_bytes", "rptq_cluster_gemm_quant_static",
     "rptq_cluster_gemm_partials", "rptq_unpack_codes", "rptq_unpack_weights", "rptq_channel_minmax",
     "rptq_cw_scale_bytes", "rptq_cw_cross_bytes", "rptq_cw_rowsum_bytes", "rptq_fold_reorder_cw", "rptq_cluster_rowsums",
@@ -67,6 +68,8 @@ def load_library():
         "rptq_fold_reorder": (i32, [vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp,
                                     vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "rptq_ln_quant": (i32, [vp, i64, i32, vp, vp, f32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "rptq_ln_quant_scatter": (i32, [vp, i64, i32, vp, vp, f32, i32, vp, vp, i32, vp, vp, i32, vp, vp, sz, vp]),
+        "rptq_ln_quant_scatter_workspace_bytes": (sz, [i64, i32, i32]),
         "rptq_cluster_gemm": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, vp]),
         "rptq_cluster_gemm_quant": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, i32,
                                           vp, i32, vp, vp, vp, i32, vp, vp, vp, sz, vp]),
@@ -294,6 +297,23 @@ def rptq_ln_quant(x, M: int, d: int, gamma_pad, beta_pad, eps: float, relu: bool
         float(eps), int(bool(relu)), _dev(perm_pad, torch.int32), poff, len(off) - 1, ps, pi, pz, bits,
         _dev(codes_packed), _dev(xsum, torch.int32, True), _dev(rowterm, torch.float32, True), _stream(stream))
     _check(st, "rptq_ln_quant")
+
+
+def rptq_ln_quant_scatter_workspace_bytes(M: int, d: int, k_padded: int) -> int:
+    return int(load_library().rptq_ln_quant_scatter_workspace_bytes(M, d, k_padded))
+
+
+def rptq_ln_quant_scatter(x, M: int, d: int, gamma, beta, eps: float, relu: bool, perm_pad, cluster_off, inv_s, z,
+                          bits: int, codes_packed, workspace, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    ia, pi = _host(inv_s, np.float32)
+    za, pz = _host(z, np.int32)
+    st = load_library().rptq_ln_quant_scatter(
+        _dev(x, torch.bfloat16), M, d, _dev(gamma, torch.float32, True), _dev(beta, torch.float32, True), float(eps),
+        int(bool(relu)), _dev(perm_pad, torch.int32), poff, len(off) - 1, pi, pz, bits, _dev(codes_packed),
+        _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "rptq_ln_quant_scatter")
 
 
 def rptq_cluster_gemm(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, sX, sW, zW, colterm,

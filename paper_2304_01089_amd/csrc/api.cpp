@@ -151,6 +151,32 @@ int32_t rptq_ln_quant(const void* x, int64_t M, int32_t d,
                          rowterm, static_cast<hipStream_t>(stream));
 }
 
+size_t rptq_ln_quant_scatter_workspace_bytes(int64_t M, int32_t d, int32_t k_padded) {
+  if (M < 0 || d < 8 || d > RPTQ_MAX_CHANNELS || k_padded < 1 || k_padded % RPTQ_K_ALIGN != 0) return 0;
+  return ln_scatter_workspace_bytes(M, d, k_padded);
+}
+
+int32_t rptq_ln_quant_scatter(const void* x, int64_t M, int32_t d, const float* gamma, const float* beta, float eps,
+                              int32_t relu, const int32_t* perm_pad, const int32_t* cluster_off, int32_t g,
+                              const float* inv_s, const int32_t* z, int32_t bits, void* codes_packed,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !perm_pad || !inv_s || !z || !codes_packed || !workspace) return RPTQ_ERR_NULL;
+  if ((gamma == nullptr) != (beta == nullptr)) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0 || d < 8 || d % 8 != 0 || geom.k != d) return RPTQ_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return RPTQ_ERR_RANGE;
+  QuantTab qt;
+  if (int32_t st = make_quant_tab(geom, nullptr, inv_s, z, bits, &qt)) return st;
+  if (workspace_bytes < ln_scatter_workspace_bytes(M, d, geom.k_padded)) return RPTQ_ERR_WORKSPACE;
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(perm_pad) || !aligned16(codes_packed) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return RPTQ_ERR_ALIGN;
+  return launch_ln_scatter(x, M, d, gamma, beta, eps, relu, perm_pad, geom, qt, bits, codes_packed, workspace,
+                           static_cast<hipStream_t>(stream));
+}
+
 int32_t rptq_cluster_gemm(const void* codes_packed, int64_t M, int32_t bits,
                           const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g,
                           const float* sX, const float* sW, const int32_t* zW,

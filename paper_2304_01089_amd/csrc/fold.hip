@@ -258,7 +258,9 @@ __global__ void __launch_bounds__(256) fold_weight_cw_kernel(FoldCwArgs a, Clust
       zz = -rint((h + l) / (2.0 * s64));
     }
     const float s32 = static_cast<float>(s64);
-    if (!(s32 >= 1.17549435e-38f && s32 <= 3.4028234664e38f) || !(fabs(zz) <= 2097152.0)) atomicOr(&g_fold_status, 2);
+    // (a block that lies far from zero relative to its width has a large zero point: at most
+    // 8 * 2 * 2^24 for fp32 extrema that differ, so it always fits an int32)
+    if (!(s32 >= 1.17549435e-38f && s32 <= 3.4028234664e38f) || !(fabs(zz) <= 1073741824.0)) atomicOr(&g_fold_status, 2);
     sh_s[tid] = s32;
     sh_inv[tid] = static_cast<float>(1.0 / static_cast<double>(s32));
     sh_z[tid] = static_cast<int32_t>(zz);
@@ -268,7 +270,8 @@ __global__ void __launch_bounds__(256) fold_weight_cw_kernel(FoldCwArgs a, Clust
   for (int u = tid; u < n_units; u += blockDim.x) {
     int ci = 0;
     for (int i = 1; i < g; ++i) ci += (u * 8 >= geom.pad_off[i]) ? 1 : 0;
-    const float inv = sh_inv[ci], zf = static_cast<float>(sh_z[ci]);
+    const float inv = sh_inv[ci];
+    const double zd = static_cast<double>(sh_z[ci]);
     int q[8];
     int sum = 0;
 #pragma unroll
@@ -276,9 +279,9 @@ __global__ void __launch_bounds__(256) fold_weight_cw_kernel(FoldCwArgs a, Clust
       const int c = a.perm_pad[u * 8 + e];
       int code = 0;
       if (c >= 0) {
-        const float r = __fmul_rn(wval(c), inv);
-        float b = __fadd_rn(rintf(r), zf);
-        b = fminf(fmaxf(b, -8.0f), 7.0f);
+        const float r = __fmul_rn(wval(c), inv);           // one fp32 rounding, as everywhere
+        double b = rint(static_cast<double>(r)) + zd;      // the zero point of a block may exceed fp32's exact integers
+        b = fmin(fmax(b, -8.0), 7.0);
         code = static_cast<int>(b);
       }
       q[e] = code;

@@ -354,9 +354,11 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
                 if (t < a.M && n < a.N) {
                   const int p = acc[i][j][r] >> (ActFmt<BITS>::kShift + 4);
                   const int zw = CWISE ? a.zW[static_cast<int64_t>(n) * tab.g + ci] : a.zW[n];
-                  const int v = p - zx * a.wsum[static_cast<int64_t>(n) * tab.g + ci] -
-                                zw * a.xsum[t * tab.g + ci] + nn * zx * zw;
-                  a.yq[(static_cast<int64_t>(ci) * a.M + t) * a.N + n] = v;
+                  // (64-bit: the zero point of a weight block far from zero can reach 2^28; the stored
+                  // value is the integer modulo 2^32)
+                  const int64_t v = static_cast<int64_t>(p) - static_cast<int64_t>(zx) * a.wsum[static_cast<int64_t>(n) * tab.g + ci] -
+                                    static_cast<int64_t>(zw) * a.xsum[t * tab.g + ci] + static_cast<int64_t>(nn) * zx * zw;
+                  a.yq[(static_cast<int64_t>(ci) * a.M + t) * a.N + n] = static_cast<int32_t>(v);
                 }
               }
               clear_tile(i, j);

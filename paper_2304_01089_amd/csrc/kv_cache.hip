@@ -171,8 +171,11 @@ int32_t launch_kv_quant(const void* x, int64_t T, int32_t d, const KvPos* pos, i
   int cus = 0;
   if (int32_t s = device_compute_units(st, &cus)) return s;
   const int segs = (d + kKvTile - 1) / kKvTile;
-  // about eight workgroups of four waves per compute unit; every workgroup keeps one tile column
+  // about eight workgroups of four waves per compute unit, but at least 32 rows per wave while the
+  // batch allows (a wave's per-lane constants cost as much as eight rows of input); every workgroup
+  // keeps one tile column
   int64_t row_groups = (static_cast<int64_t>(cus) * 8 + segs - 1) / segs;
+  row_groups = std::min<int64_t>(row_groups, std::max<int64_t>((T + 127) / 128, (static_cast<int64_t>(cus) * 2 + segs - 1) / segs));
   row_groups = std::min<int64_t>(std::max<int64_t>(row_groups, 1), (T + 3) / 4);
   const dim3 grid(static_cast<unsigned>(segs * row_groups)), block(256);
   const uint4* xp = static_cast<const uint4*>(x);
@@ -189,7 +192,9 @@ int32_t launch_kv_dequant(const void* codes, int64_t T, int32_t d, const KvPos* 
   int cus = 0;
   if (int32_t s = device_compute_units(st, &cus)) return s;
   const int blocks_per_row = (d / kGroup + 127) / 128;
+  // (a thread's constants are 512 bytes: at least 32 rows per thread while the batch allows)
   int64_t rows_par = (static_cast<int64_t>(cus) * 16 + blocks_per_row - 1) / blocks_per_row;
+  rows_par = std::min<int64_t>(rows_par, std::max<int64_t>((T + 31) / 32, (static_cast<int64_t>(cus) * 4 + blocks_per_row - 1) / blocks_per_row));
   rows_par = std::min<int64_t>(std::max<int64_t>(rows_par, 1), T);
   const dim3 grid(static_cast<unsigned>(blocks_per_row * rows_par)), block(128);
   const uint8_t* cp = static_cast<const uint8_t*>(codes);

@@ -129,6 +129,10 @@ int32_t launch_cluster_rowsums(const void* codes, int64_t M, const ClusterGeom& 
 size_t gemm_quant_workspace_bytes(int64_t M, int32_t N);
 // Device address of the library's static scratch array on the current device (gemm.hip).
 int32_t gemm_static_scratch(void** ptr);
+size_t ln_scatter_workspace_bytes(int64_t M, int32_t d, int32_t k_padded);
+int32_t launch_ln_scatter(const void* x, int64_t M, int32_t d, const float* gamma, const float* beta, float eps,
+                          int32_t relu, const int32_t* perm_pad, const ClusterGeom& geom, const QuantTab& qt, int32_t bits,
+                          void* codes, void* workspace, hipStream_t st);
 int32_t launch_unpack_codes(const void* codes, int64_t rows, const ClusterGeom& geom, int32_t bits, int8_t* out,
                             hipStream_t st);
 int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st);

@@ -301,3 +301,26 @@ def test_deterministic_across_runs(rp):
         rp.rptq_cluster_gemm(codes, c.M, c.bits, Wq, c.N, cal.cluster_off, cal.s, sW, zW, colterm, rowterm, y)
         outs.append(y.cpu().numpy())
     assert np.array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("name", ["tiny_a4", "tiny_a3", "tiny_a8", "relu_site", "mid_a3", "mid_a4", "one_row", "deep_a3"])
+def test_scatter_on_write_variant_gives_the_same_codes(rp, name):
+    """Sec. 4.2's own wording of the fused reorder (LayerNorm in the original order, the reorder index
+    offsets the write address) as a second implementation: packed codes identical to rptq_ln_quant's."""
+    c = get_case(name)
+    cal = c.cal
+    k_p, perm_pad, gpad, bpad = _folded_site(rp, c)
+    x = dev_bf16(c.site.x)
+    codes = torch.empty(rp.rptq_codes_bytes(c.M, k_p, c.bits), dtype=torch.uint8, device="cuda")
+    rp.rptq_ln_quant(x, c.M, c.d, gpad, bpad, EPS, c.relu, perm_pad, cal.cluster_off, cal.s, cal.inv_s, cal.z,
+                     c.bits, codes, None, None)
+    ws = torch.empty(rp.rptq_ln_quant_scatter_workspace_bytes(c.M, c.d, k_p) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    codes2 = torch.full_like(codes, 0x5A)
+    rp.rptq_ln_quant_scatter(x, c.M, c.d, dev(c.gamma) if c.ln else None, dev(c.beta) if c.ln else None, EPS, c.relu,
+                             perm_pad, cal.cluster_off, cal.inv_s, cal.z, c.bits, codes2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(codes, codes2)
+    got, pads = packfmt.unpack_codes(codes2.cpu().numpy().reshape(c.M, -1), cal.cluster_off, c.bits)
+    ok = ~c.fragile
+    assert (pads == 0).all() and np.array_equal(got[ok], c.codes[ok])
