@@ -265,7 +265,12 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     if (LN) *reinterpret_cast<double2*>(part12 + (static_cast<size_t>(pb) * TU + tid) * 2) = make_double2(s1, s2);
   };
 
-  const float relu_floor = a.relu ? 0.0f : -__builtin_huge_valf();
+  // ReLU commutes with the rounding and with the (monotonic, exact) addition of the zero point:
+  // max(y, 0) before Eq. 1 equals a lower clamp of the biased code at the biased zero point, which
+  // shares one median-of-three instruction with the upper clamp.
+  float code_floor[NUNIT];
+#pragma unroll
+  for (int n = 0; n < NUNIT; ++n) code_floor[n] = a.relu ? fminf(zbf[n], kUMax) : -__builtin_huge_valf();   // (zero points beyond the range: floor at the top code)
 
   // ---- pipelined row loop --------------------------------------------------------------------
   int b_cur = 0, b_next = lds.rowbuf_bytes, b_spare = (a.ring == 3) ? 2 * lds.rowbuf_bytes : 0;
@@ -301,10 +306,10 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
         const uint32_t h = *reinterpret_cast<const uint16_t*>(rowbuf + src[n][e]);
         float y = __uint_as_float(h << 16);
         if (LN) y = ln_chain(y, mu, rstd, gam[n][e], bet[n][e]);
-        y = fmaxf(y, relu_floor);                        // ReLU sites: 0; otherwise -inf (no effect)
         const float r = __fmul_rn(y, inv_s[n]);
         float b = __fadd_rn(rintf(r), zbf[n]);          // round, then add the zero point (biased by -qmin)
-        if (BITS < 8) b = fminf(b, kUMax);              // upper clamp; the conversion saturates at 0 and 255
+        // ReLU floor (or -inf) and upper clamp; the conversion saturates at 0 and 255
+        b = (BITS < 8) ? __builtin_amdgcn_fmed3f(b, code_floor[n], kUMax) : fmaxf(b, code_floor[n]);
         D[e / 4] = __builtin_amdgcn_cvt_pk_u8_f32(b, e & 3, D[e / 4]);
       }
 #pragma unroll
