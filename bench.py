@@ -277,12 +277,13 @@ def main():
                 stage_info["gemm:%s" % lin["name"]] = dict(bound="mfma", work=ops, unit="TOP/s", peak=PEAK_INT8_TOPS, scale=1e-12)
     # the same peaks from what the box reports: compute units x clock x 8192 int8 ops per clock and
     # unit (the 32x32x32 int8 MFMA: 65536 ops in 16 passes of 4 clocks on each of 4 matrix cores);
-    # memory clock x bus width x 2 transfers per clock
+    # memory clock x bus width x 4 transfers per reported clock (HBM3E: 8 Gb/s per pin at the 2000 MHz the
+    # runtime reports; 8192 pins)
     di = rp.rptq_device_info()
     box = dict(compute_units=di["compute_units"], clock_mhz=round(di["clock_khz"] / 1e3, 1),
                int8_tops=round(di["compute_units"] * di["clock_khz"] * 1e3 * 8192 / 1e12, 1),
                memory_clock_mhz=round(di["memory_clock_khz"] / 1e3, 1), memory_bus_bits=di["memory_bus_bits"],
-               hbm_gbs=round(di["memory_clock_khz"] * 1e3 * 2 * di["memory_bus_bits"] / 8 / 1e9, 1))
+               hbm_gbs=round(di["memory_clock_khz"] * 1e3 * 4 * di["memory_bus_bits"] / 8 / 1e9, 1))
     dominant = max(stage_avg, key=lambda k: stage_avg[k])
     info = stage_info[dominant]
     achieved = info["work"] / (stage_avg[dominant] * 1e-3) * info["scale"]

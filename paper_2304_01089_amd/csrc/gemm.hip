@@ -205,6 +205,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   // with a lane read, no memory access inside the loop
   const float tab_scale = tab.scale[lane];
   const int tab_end = tab.slice_end[lane];
+  const int tab_zx = PARTIALS ? tab.zx[lane] : 0, tab_n = PARTIALS ? tab.n[lane] : 0;
   int ci = 0;
   int next_end = __builtin_amdgcn_readlane(tab_end, 0);
   const int steps = (a.used_slices + kStepSlices - 1) / kStepSlices;
@@ -342,7 +343,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       const int gs = step * kStepSlices + s + 1;           // slices accumulated so far
       if (gs == next_end) {                                  // cluster ci is complete (uniform branch)
         if (PARTIALS) {
-          const int zx = tab.zx[ci], nn = tab.n[ci];
+          const int zx = __builtin_amdgcn_readlane(tab_zx, ci), nn = __builtin_amdgcn_readlane(tab_n, ci);
 #pragma unroll
           for (int i = 0; i < WM; ++i)
 #pragma unroll

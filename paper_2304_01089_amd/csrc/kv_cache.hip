@@ -59,9 +59,6 @@ __global__ void __launch_bounds__(256) kv_quant_kernel(const uint4* x, int64_t T
   const bool lane_ok = (BITS == 3) ? ((lane >> 1) * kGroup < n_here) : (lane * kKvLaneCodes < n_here);
   // this lane's two 16-byte chunks of the tile's input (clamped inside the tile; surplus data is never gathered)
   const int chunks_here = n_here / 8;
-  int ch[2];
-#pragma unroll
-  for (int c = 0; c < 2; ++c) ch[c] = (c * 64 + lane) < chunks_here ? (c * 64 + lane) : (chunks_here - 1);
   const int64_t row_chunks = d / 8;
   const int64_t stride = static_cast<int64_t>(row_groups) * 4;
   int64_t row = static_cast<int64_t>(rg) * 4 + wave;
@@ -69,21 +66,26 @@ __global__ void __launch_bounds__(256) kv_quant_kernel(const uint4* x, int64_t T
   const int64_t out_row_bytes = static_cast<int64_t>(d) * BITS / 8;
   const int64_t out_tile = static_cast<int64_t>(base_ch) * BITS / 8;
 
-  auto fetch = [&](int64_t r, uint4* dst) {
+  // (scalars, not arrays handed to a helper by pointer: those ended up in scratch memory, re-written
+  // every row)
+  const int ch0 = lane < chunks_here ? lane : (chunks_here - 1);
+  const int ch1 = (64 + lane) < chunks_here ? (64 + lane) : (chunks_here - 1);
+  auto row_ptr = [&](int64_t r) {
     if (r >= T) r = T - 1;
-    const uint4* p = x + r * row_chunks + base_ch / 8;
-#pragma unroll
-    for (int c = 0; c < 2; ++c) dst[c] = p[ch[c]];
+    return x + r * row_chunks + base_ch / 8;
   };
-  uint4 cur[2], nxt[2];
-  fetch(row, cur);
-  fetch(row + stride, nxt);
+  const uint4* p0 = row_ptr(row);
+  uint4 cur0 = p0[ch0], cur1 = p0[ch1];
+  const uint4* p1 = row_ptr(row + stride);
+  uint4 nxt0 = p1[ch0], nxt1 = p1[ch1];
   for (; row < T; row += stride) {
-#pragma unroll
-    for (int c = 0; c < 2; ++c) *reinterpret_cast<uint4*>(my + (c * 64 + lane) * 16) = cur[c];
-#pragma unroll
-    for (int c = 0; c < 2; ++c) cur[c] = nxt[c];
-    fetch(row + 2 * stride, nxt);
+    *reinterpret_cast<uint4*>(my + lane * 16) = cur0;
+    *reinterpret_cast<uint4*>(my + (64 + lane) * 16) = cur1;
+    cur0 = nxt0;
+    cur1 = nxt1;
+    const uint4* p2 = row_ptr(row + 2 * stride);
+    nxt0 = p2[ch0];
+    nxt1 = p2[ch1];
     __builtin_amdgcn_wave_barrier();                 // (one wave: LDS executes its instructions in order)
     uint32_t D[4] = {0u, 0u, 0u, 0u};                // biased codes, one byte each
 #pragma unroll
@@ -138,8 +140,9 @@ __global__ void __launch_bounds__(128) kv_dequant_kernel(const uint8_t* codes, i
   }
   const int64_t row_bytes = static_cast<int64_t>(d) * BITS / 8;
   const int64_t stride = gridDim.x / blocks_per_row;
-  for (int64_t row = blockIdx.x / blocks_per_row; row < T; row += stride) {
-    uint32_t w[GB / 4];
+  // the next row's codes are requested before this row is expanded (rows past the end: the last row again)
+  auto load_row = [&](int64_t row, uint32_t (&w)[GB / 4]) {
+    if (row >= T) row = T - 1;
     const uint32_t* p = reinterpret_cast<const uint32_t*>(codes + row * row_bytes + static_cast<int64_t>(gi) * GB);
     if constexpr (BITS == 3) {
       w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
@@ -150,6 +153,12 @@ __global__ void __launch_bounds__(128) kv_dequant_kernel(const uint8_t* codes, i
         w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
       }
     }
+  };
+  uint32_t w[GB / 4], wn[GB / 4];
+  int64_t row = blockIdx.x / blocks_per_row;
+  load_row(row, w);
+  for (; row < T; row += stride) {
+    load_row(row + stride, wn);
     int q[32];
     decode_group<BITS>(w, q);
     uint32_t o[16];
@@ -163,6 +172,8 @@ __global__ void __launch_bounds__(128) kv_dequant_kernel(const uint8_t* codes, i
     uint4* dst = reinterpret_cast<uint4*>(out + row * d + static_cast<int64_t>(gi) * kGroup);
 #pragma unroll
     for (int k = 0; k < 4; ++k) dst[k] = make_uint4(o[4 * k], o[4 * k + 1], o[4 * k + 2], o[4 * k + 3]);
+#pragma unroll
+    for (int k = 0; k < GB / 4; ++k) w[k] = wn[k];
   }
 }
 
@@ -192,9 +203,9 @@ int32_t launch_kv_dequant(const void* codes, int64_t T, int32_t d, const KvPos* 
   int cus = 0;
   if (int32_t s = device_compute_units(st, &cus)) return s;
   const int blocks_per_row = (d / kGroup + 127) / 128;
-  // (a thread's constants are 512 bytes: at least 32 rows per thread while the batch allows)
+  // (a thread's constants are 512 bytes: at least 16 rows per thread while the batch allows)
   int64_t rows_par = (static_cast<int64_t>(cus) * 16 + blocks_per_row - 1) / blocks_per_row;
-  rows_par = std::min<int64_t>(rows_par, std::max<int64_t>((T + 31) / 32, (static_cast<int64_t>(cus) * 4 + blocks_per_row - 1) / blocks_per_row));
+  rows_par = std::min<int64_t>(rows_par, std::max<int64_t>((T + 15) / 16, (static_cast<int64_t>(cus) * 4 + blocks_per_row - 1) / blocks_per_row));
   rows_par = std::min<int64_t>(std::max<int64_t>(rows_par, 1), T);
   const dim3 grid(static_cast<unsigned>(blocks_per_row * rows_par)), block(128);
   const uint8_t* cp = static_cast<const uint8_t*>(codes);

@@ -21,10 +21,10 @@ __global__ void invert_perm_pad_kernel(const int32_t* perm_pad, int32_t k_padded
   if (c >= 0) dst[c] = j;
 }
 
-constexpr int kScChunk = 4;       // 16-byte chunks of the input row per thread
-
-template <bool LN>
-__global__ void __launch_bounds__(1024) ln_scatter_kernel(const uint4* x, int64_t M, int32_t d, const float* gamma,
+// kScChunk: 16-byte chunks of the input row per thread (4 up to 16384 channels, 8 beyond); at most
+// 512 threads, so that a thread's constants fit the register file
+template <bool LN, int kScChunk>
+__global__ void __launch_bounds__(512) ln_scatter_kernel(const uint4* x, int64_t M, int32_t d, const float* gamma,
                                                           const float* beta, float eps, int32_t relu, const int32_t* dst,
                                                           ClusterGeom geom, QuantTab qt, int32_t qmin, int8_t* out) {
   __shared__ double red[2][2][kMaxWaves];
@@ -57,20 +57,20 @@ __global__ void __launch_bounds__(1024) ln_scatter_kernel(const uint4* x, int64_
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll
     for (int c = 0; c < kScChunk; ++c) {
+      // (no load under a lane-dependent branch: surplus lanes read a valid chunk again and add zeros)
       const int idx = tid + c * T;
-      if (idx < chunks) {
-        v[c] = x[row * chunks + idx];
-        if (LN) {
-          const uint32_t w[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+      const bool ok = idx < chunks;
+      v[c] = x[row * chunks + (ok ? idx : chunks - 1)];
+      if (LN) {
+        const uint32_t w[4] = {ok ? v[c].x : 0u, ok ? v[c].y : 0u, ok ? v[c].z : 0u, ok ? v[c].w : 0u};
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const double lo = static_cast<double>(bf16_lo(w[k]));
-            const double hi = static_cast<double>(bf16_hi(w[k]));
-            s1 += lo;
-            s2 = fma(lo, lo, s2);
-            s1 += hi;
-            s2 = fma(hi, hi, s2);
-          }
+        for (int k = 0; k < 4; ++k) {
+          const double lo = static_cast<double>(bf16_lo(w[k]));
+          const double hi = static_cast<double>(bf16_hi(w[k]));
+          s1 += lo;
+          s2 = fma(lo, lo, s2);
+          s1 += hi;
+          s2 = fma(hi, hi, s2);
         }
       }
     }
@@ -188,16 +188,19 @@ int32_t launch_ln_scatter(const void* x, int64_t M, int32_t d, const float* gamm
   hipLaunchKernelGGL(invert_perm_pad_kernel, dim3((geom.k_padded + 255) / 256), dim3(256), 0, st, perm_pad, geom.k_padded, dst);
   RPTQ_HIP(hipGetLastError());
   const int chunks = d / 8;
-  int threads = ((chunks + kScChunk - 1) / kScChunk + kWave - 1) / kWave * kWave;
+  const int per_thread = chunks <= 512 * 4 ? 4 : 8;
+  int threads = ((chunks + per_thread - 1) / per_thread + kWave - 1) / kWave * kWave;
   if (threads < 256) threads = std::min(256, (chunks + kWave - 1) / kWave * kWave);
-  if (threads > 1024) return RPTQ_ERR_SHAPE;
+  if (threads > 512) return RPTQ_ERR_SHAPE;
   int cus = 0;
   if (int32_t s = device_compute_units(st, &cus)) return s;
   const int grid = static_cast<int>(std::min<int64_t>(M, static_cast<int64_t>(cus) * 2));
   const int qmin = -(1 << (bits - 1));
   const uint4* xp = static_cast<const uint4*>(x);
-  if (gamma) hipLaunchKernelGGL(ln_scatter_kernel<true>, dim3(grid), dim3(threads), 0, st, xp, M, d, gamma, beta, eps, relu, dst, geom, qt, qmin, bytes);
-  else hipLaunchKernelGGL(ln_scatter_kernel<false>, dim3(grid), dim3(threads), 0, st, xp, M, d, gamma, beta, eps, relu, dst, geom, qt, qmin, bytes);
+  if (gamma && per_thread == 4) hipLaunchKernelGGL((ln_scatter_kernel<true, 4>), dim3(grid), dim3(threads), 0, st, xp, M, d, gamma, beta, eps, relu, dst, geom, qt, qmin, bytes);
+  else if (gamma) hipLaunchKernelGGL((ln_scatter_kernel<true, 8>), dim3(grid), dim3(threads), 0, st, xp, M, d, gamma, beta, eps, relu, dst, geom, qt, qmin, bytes);
+  else if (per_thread == 4) hipLaunchKernelGGL((ln_scatter_kernel<false, 4>), dim3(grid), dim3(threads), 0, st, xp, M, d, gamma, beta, eps, relu, dst, geom, qt, qmin, bytes);
+  else hipLaunchKernelGGL((ln_scatter_kernel<false, 8>), dim3(grid), dim3(threads), 0, st, xp, M, d, gamma, beta, eps, relu, dst, geom, qt, qmin, bytes);
   RPTQ_HIP(hipGetLastError());
   const int64_t total = M * (geom.k_padded / kGroup);
   const int pgrid = static_cast<int>(std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(cus) * 16));
