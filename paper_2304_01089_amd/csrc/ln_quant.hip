@@ -12,6 +12,8 @@
 // in cluster order, run the fp32 LayerNorm chain, round/offset/clamp, pack and store.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "device_common.h"
 #include "pack_formats.h"
 #include "rptq_internal.h"
@@ -55,9 +57,12 @@ struct LnLds {
   int rowbuf_bytes;
   int part12, part3, bcast;          // byte offsets
 };
-__host__ __device__ inline LnLds ln_lds_layout(int d, int ring, int tu) {
+// Row-buffer stride of the kernels with compile-time buffer offsets: the offset of the third
+// buffer still fits the 16-bit offset field of an LDS instruction.
+constexpr int kFixedStride = 32752;
+__host__ __device__ inline LnLds ln_lds_layout(int d, int ring, int tu, bool fixed = false) {
   LnLds l;
-  l.rowbuf_bytes = d * 2 + 16;
+  l.rowbuf_bytes = fixed ? kFixedStride : d * 2 + 16;
   l.part12 = ring * l.rowbuf_bytes;
   l.part3 = l.part12 + 2 * tu * 16;
   l.bcast = l.part3 + 2 * tu * 8;
@@ -67,7 +72,12 @@ __host__ __device__ inline LnLds ln_lds_layout(int d, int ring, int tu) {
 // No load of this kernel sits under a lane-dependent branch: indices are clamped and what a
 // surplus lane computes is masked or never stored.  (A load under a divergent branch makes
 // the compiler wait for every load in flight at each such branch, which serializes them.)
-template <int BITS, int NUNIT, int NCH, bool LN>
+//
+// FIXED (wide LayerNorm rows, three row buffers at the constant stride kFixedStride): the row loop
+// is unrolled over the three buffers, so a gather read carries its buffer's offset in the
+// instruction instead of adding it to the address, and the 16-bit reads land in the upper half of
+// their registers (the bf16 value as fp32, no shift).  Two vector instructions less per element.
+template <int BITS, int NUNIT, int NCH, bool LN, bool FIXED = false>
 __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGeom geom, QuantTab qt) {
   constexpr int UC = Unit<BITS>::kCodes;
   constexpr int ND = UC / 4;                       // dwords of biased code bytes per unit
@@ -81,7 +91,7 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   const int TU = static_cast<int>(blockDim.x) - kWave;          // unit threads; the last wave does the statistics
   const int nwu = TU >> 6;
   const bool stats_wave = wid == nwu;
-  const LnLds lds = ln_lds_layout(a.d, a.ring, TU);
+  const LnLds lds = ln_lds_layout(a.d, a.ring, TU, FIXED);
   double* part12 = reinterpret_cast<double*>(smem + lds.part12);   // [2][TU][2]
   double* part3 = reinterpret_cast<double*>(smem + lds.part3);     // [2][TU]
   float* bcast = reinterpret_cast<float*>(smem + lds.bcast);       // [2][2]
@@ -280,16 +290,44 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
 
   // one iteration: stage row i+1 from `regs`, request the next row they will hold (i+3, or
   // i+2 with one set), then gather row i
-  auto row_iter = [&](int i, uint4* regs) {
-    stage_row(regs, smem + b_next, (i + 1) & 1);
+  // destination registers of the upper-half LDS reads (FIXED): only those reads ever write them
+  uint32_t hreg[FIXED ? NUNIT : 1][FIXED ? UC : 1];
+#pragma unroll
+  for (int n = 0; n < (FIXED ? NUNIT : 1); ++n)
+#pragma unroll
+    for (int e = 0; e < (FIXED ? UC : 1); ++e) hreg[n][e] = 0u;
+
+  // bc_tag: the row buffer that holds row i when it is known at compile time (FIXED), else -1
+  auto row_iter = [&](int i, uint4* regs, auto bc_tag) {
+    constexpr int BC = decltype(bc_tag)::value;
+    const int cur_off = BC >= 0 ? BC * kFixedStride : b_cur;
+    const int next_off = BC >= 0 ? ((BC + 1) % 3) * kFixedStride : b_next;
+    stage_row(regs, smem + next_off, (i + 1) & 1);
     fetch_row(i + (kDeep ? 3 : 2), regs);
     __syncthreads();                                           // row i+1 staged; {mean, 1/std} of row i published
-    const unsigned char* rowbuf = smem + b_cur;
+    const unsigned char* rowbuf = smem + cur_off;
     float mu = 0.0f, rstd = 1.0f;
     if (LN) {
       const float2 ms = *reinterpret_cast<const float2*>(bcast + (i & 1) * 2);
       mu = ms.x;
       rstd = ms.y;
+    }
+    if constexpr (BC >= 0) {
+      // all of this thread's source values at once; the wait below also ties every later use of
+      // the registers to the reads' completion
+#pragma unroll
+      for (int n = 0; n < NUNIT; ++n)
+#pragma unroll
+        for (int e = 0; e < UC; ++e)
+          asm volatile("ds_read_u16_d16_hi %0, %1 offset:%2" : "+v"(hreg[n][e]) : "v"(src[n][e]), "n"(BC * kFixedStride));
+      static_assert(!FIXED || NUNIT * UC == 16, "sixteen source values per thread");
+      uint32_t(&h)[FIXED ? NUNIT : 1][FIXED ? UC : 1] = hreg;
+      constexpr int U = FIXED ? UC : 1;
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(h[0 / U][0 % U]), "+v"(h[1 / U][1 % U]), "+v"(h[2 / U][2 % U]), "+v"(h[3 / U][3 % U]),
+                     "+v"(h[4 / U][4 % U]), "+v"(h[5 / U][5 % U]), "+v"(h[6 / U][6 % U]), "+v"(h[7 / U][7 % U]),
+                     "+v"(h[8 / U][8 % U]), "+v"(h[9 / U][9 % U]), "+v"(h[10 / U][10 % U]), "+v"(h[11 / U][11 % U]),
+                     "+v"(h[12 / U][12 % U]), "+v"(h[13 / U][13 % U]), "+v"(h[14 / U][14 % U]), "+v"(h[15 / U][15 % U]));
     }
     const int64_t row = row0 + i * stride;
 
@@ -303,8 +341,13 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
       for (int w = 0; w < ND; ++w) D[w] = 0u;
 #pragma unroll
       for (int e = 0; e < UC; ++e) {
-        const uint32_t h = *reinterpret_cast<const uint16_t*>(rowbuf + src[n][e]);
-        float y = __uint_as_float(h << 16);
+        float y;
+        if constexpr (BC >= 0) {
+          y = __uint_as_float(hreg[n][e]);
+        } else {
+          const uint32_t h = *reinterpret_cast<const uint16_t*>(rowbuf + src[n][e]);
+          y = __uint_as_float(h << 16);
+        }
         if (LN) y = ln_chain(y, mu, rstd, gam[n][e], bet[n][e]);
         const float r = __fmul_rn(y, inv_s[n]);
         float b = __fadd_rn(rintf(r), zbf[n]);          // round, then add the zero point (biased by -qmin)
@@ -343,6 +386,7 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
       }
     }
     part3[static_cast<size_t>(i & 1) * TU + tid] = rt;
+    if (BC >= 0) return;
     if (a.ring == 2) {
       __syncthreads();                                         // two row buffers only: all gathers done before the next staging
       const int t = b_cur; b_cur = b_next; b_next = t;
@@ -350,15 +394,30 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
       const int t = b_cur; b_cur = b_next; b_next = b_spare; b_spare = t;
     }
   };
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
+  using B2 = std::integral_constant<int, 2>;
+  using BR = std::integral_constant<int, -1>;
   if (kDeep) {
     int i = 0;
-    for (; i + 1 < n_rows; i += 2) {                           // row i+1 waits in nxb, row i+2 in nxa
-      row_iter(i, nxb);
-      row_iter(i + 1, nxa);
+    if (FIXED) {                                               // six rows per pass: 2 register sets x 3 buffers
+      for (; i + 5 < n_rows; i += 6) {
+        row_iter(i, nxb, B0());
+        row_iter(i + 1, nxa, B1());
+        row_iter(i + 2, nxb, B2());
+        row_iter(i + 3, nxa, B0());
+        row_iter(i + 4, nxb, B1());
+        row_iter(i + 5, nxa, B2());
+      }
+      // (the last rows take the run-time offsets below, which start at buffer 0 again)
     }
-    if (i < n_rows) row_iter(i, nxb);
+    for (; i + 1 < n_rows; i += 2) {                           // row i+1 waits in nxb, row i+2 in nxa
+      row_iter(i, nxb, BR());
+      row_iter(i + 1, nxa, BR());
+    }
+    if (i < n_rows) row_iter(i, nxb, BR());
   } else {
-    for (int i = 0; i < n_rows; ++i) row_iter(i, nxa);
+    for (int i = 0; i < n_rows; ++i) row_iter(i, nxa, BR());
   }
   __syncthreads();                                             // last row's partial sums are in LDS
 }
@@ -463,10 +522,10 @@ __global__ void unpack_codes_kernel(const uint8_t* codes, int64_t rows, int32_t 
 constexpr int kMaxChunk = 4;   // 16-byte chunks of the input row per unit thread
 constexpr int kMaxUnitThreads = 1024 - kWave;
 
-template <int BITS, int NUNIT, int NCH, bool LN>
+template <int BITS, int NUNIT, int NCH, bool LN, bool FIXED = false>
 static int32_t launch_kernel(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, int threads,
                              int64_t want_grid, int lds_per_cu, size_t shmem, hipStream_t st) {
-  auto kern = ln_quant_kernel<BITS, NUNIT, NCH, LN>;
+  auto kern = ln_quant_kernel<BITS, NUNIT, NCH, LN, FIXED>;
   static LdsGrant lds_granted;
   if (int32_t st_lds = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shmem, &lds_granted, st)) return st_lds;
   // workgroups resident per compute unit (registers, threads, LDS); the grid is one full round
@@ -484,6 +543,18 @@ static int32_t launch_kernel(const LnQuantArgs& a, const ClusterGeom& geom, cons
 template <int BITS, int NUNIT, bool LN>
 static int32_t launch_chunks(const LnQuantArgs& a, const ClusterGeom& geom, const QuantTab& qt, int nch, int threads,
                              int64_t cus, int lds_per_cu, size_t shmem, hipStream_t st) {
+  if constexpr (LN && BITS == 3 && NUNIT == 1) {       // (the 4- and 8-bit kernels with two units per thread would spill)
+    // wide LayerNorm rows (one workgroup per compute unit either way): the variant with compile-time
+    // row-buffer offsets, when its three buffers at the fixed stride fit
+    const int rowbuf = a.d * 2 + 16;
+    const LnLds lay = ln_lds_layout(a.d, 3, threads - kWave, true);
+    const size_t shmem_fixed = static_cast<size_t>(lay.bcast) + 16;
+    if (a.ring == 3 && nch <= 2 && rowbuf > kFixedStride / 2 && rowbuf <= kFixedStride &&
+        shmem_fixed <= static_cast<size_t>(lds_per_cu)) {
+      if (nch <= 1) return launch_kernel<BITS, NUNIT, 1, true, true>(a, geom, qt, threads, cus, lds_per_cu, shmem_fixed, st);
+      return launch_kernel<BITS, NUNIT, 2, true, true>(a, geom, qt, threads, cus, lds_per_cu, shmem_fixed, st);
+    }
+  }
   if (nch <= 1) return launch_kernel<BITS, NUNIT, 1, LN>(a, geom, qt, threads, cus, lds_per_cu, shmem, st);
   if (nch == 2) return launch_kernel<BITS, NUNIT, 2, LN>(a, geom, qt, threads, cus, lds_per_cu, shmem, st);
   return launch_kernel<BITS, NUNIT, kMaxChunk, LN>(a, geom, qt, threads, cus, lds_per_cu, shmem, st);
