@@ -96,8 +96,19 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   const int total = tiles_m * tiles_n;
   int lin = blockIdx.x;
   if (total % 8 == 0) lin = (lin & 7) * (total >> 3) + (lin >> 3);
-  const int64_t m0 = static_cast<int64_t>(lin % tiles_m) * BM;
-  const int n0 = (lin / tiles_m) * BN;
+  // The workgroups resident on an XCD at one time (64 with two per compute unit) should share
+  // operands in its L2: they cover 16 row tiles x 4 column tiles (5 MB + 6.7 MB of operands at
+  // K = 12288) rather than 64 row tiles x 1 column tile (20 MB + 1.7 MB).
+  int tm = lin % tiles_m, tn = lin / tiles_m;
+  if (tiles_m % 16 == 0) {
+    const int group = lin / (4 * tiles_m), rem = lin % (4 * tiles_m);
+    const int wg = (tiles_n - 4 * group) < 4 ? (tiles_n - 4 * group) : 4;      // column tiles of this group
+    const int chunk = rem / (16 * wg), r = rem % (16 * wg);
+    tm = chunk * 16 + r / wg;
+    tn = 4 * group + r % wg;
+  }
+  const int64_t m0 = static_cast<int64_t>(tm) * BM;
+  const int n0 = tn * BN;
 
   // ---- global -> register staging ------------------------------------------------------
   uint32_t ra[2][A_PER][A_REGS];                          // two staging sets: loads run ahead of use
@@ -637,7 +648,7 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
       for (; m >= 1; m >>= 1) total += __shfl_xor(total, m, kWave);
       constexpr int LPP = CPR / NPASS;                      // lanes per pass
       const int64_t t = m0 + (cc / LPP) * RPP + rr;
-      if ((cc % LPP) == 0 && t < a.M) qo.rt_part[static_cast<int64_t>(lin / tiles_m) * a.M + t] = total;
+      if ((cc % LPP) == 0 && t < a.M) qo.rt_part[static_cast<int64_t>(tn) * a.M + t] = total;
     }
   }
 }
