@@ -112,11 +112,7 @@ def kv_quant(x, hc: HeadClusters, tensor: int, k: int):
     return o.quantize(a, inv[None, :], z[None, :], k)
 
 
-def round_to_bf16(x32: np.ndarray) -> np.ndarray:
-    """fp32 -> nearest bf16 (ties to even), returned as fp32."""
-    u = np.ascontiguousarray(x32, dtype=F32).view(np.uint32)
-    r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
-    return (r & np.uint32(0xFFFF0000)).view(F32)
+round_to_bf16 = o.round_to_bf16      # fp32 -> nearest bf16 (ties to even), returned as fp32
 
 
 def kv_dequant(codes, hc: HeadClusters, tensor: int, original_order: bool = False):

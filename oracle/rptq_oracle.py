@@ -43,6 +43,10 @@ Parity status of each function (what pins it, in tests/test_oracle_*.py):
   per-(output, cluster) weight parameters) ... triple loop; method 1 ==
   method 2; reduces to cluster_gemm_int when every cluster of a row carries
   the row's pair                                              -> pinned
+* round_to_bf16 / dequantize_bf16 / cluster_gemm_dequant_bf16 (App. A.4,
+  method 1 on bf16 operands) ... exact rational rounding on samples and ties;
+  identical to cluster_gemm_dequant when every de-quantized value is a bf16
+  number; otherwise within the rounding bound of two bf16 operands -> pinned
 """
 from __future__ import annotations
 
@@ -484,6 +488,35 @@ def cluster_gemm_dequant(xq, wq, cluster_off, sX, zX, sW, zW):
     xh = sx_col[None, :] * (np.asarray(xq, dtype=F64) - zx_col[None, :])
     wh = np.asarray(sW, dtype=F64)[:, None] * (np.asarray(wq, dtype=F64) - np.asarray(zW, dtype=F64)[:, None])
     return xh @ wh.T
+
+
+def round_to_bf16(x32):
+    """fp32 -> nearest bf16 (ties to even), returned as fp32."""
+    u = np.ascontiguousarray(x32, dtype=F32).view(np.uint32)
+    r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (r & np.uint32(0xFFFF0000)).view(F32)
+
+
+def dequantize_bf16(q, s, z):
+    """x_hat = s (x_q - z) (the line under Eq. 1) held as bf16: the integer
+    difference is exact in fp32, the product with the fp32 scale is rounded once
+    to fp32 and once more to bf16 (ties to even).  Returns fp32 holding bf16 values."""
+    n = (np.asarray(q, dtype=np.int64) - np.asarray(z, dtype=np.int64)).astype(F32)
+    return round_to_bf16(np.asarray(s, dtype=F32) * n)
+
+
+def cluster_gemm_dequant_bf16(xq, wq, cluster_off, sX, zX, sW, zW):
+    """Method 1 of App. A.4 on 16-bit floating-point operands: both tensors are
+    de-quantized to bf16 (dequantize_bf16) and multiplied, Y = X_hat W_hat^T.  The
+    product itself is exact here (fp64 of bf16 values: every term has 16
+    significant bits); the GPU accumulates it in fp32.
+    Returns (X_hat fp32 [M,K], W_hat fp32 [N,K], Y float64 [M,N])."""
+    sizes = np.diff(cluster_off)
+    sx_col = np.repeat(np.asarray(sX, dtype=F32), sizes)
+    zx_col = np.repeat(np.asarray(zX, dtype=np.int64), sizes)
+    xh = dequantize_bf16(xq, sx_col[None, :], zx_col[None, :])
+    wh = dequantize_bf16(wq, np.asarray(sW, dtype=F32)[:, None], np.asarray(zW, dtype=np.int64)[:, None])
+    return xh, wh, xh.astype(F64) @ wh.astype(F64).T
 
 
 def cluster_gemm_int(xq, wq, cluster_off, sX, zX, sW, zW):

@@ -216,3 +216,72 @@ def test_per_cluster_weight_product_both_methods_and_brute_force():
     Yq_b, Y_b = o.cluster_gemm_int_pc(codes, wqr, cal.cluster_off, cal.s, cal.z,
                                       np.repeat(sr[:, None], cal.g_eff, axis=1), np.repeat(zr[:, None], cal.g_eff, axis=1))
     assert np.array_equal(Yq_r, Yq_b) and np.allclose(Y_r, Y_b, rtol=1e-13, atol=0)
+
+
+# ---------------------------------------------------------------------------
+# App. A.4, first method, on bf16 operands
+# ---------------------------------------------------------------------------
+def _bf16_nearest_even_exact(v: float) -> float:
+    """Nearest bf16 (8 significant bits) to a double, ties to even, by exact rational arithmetic."""
+    from fractions import Fraction
+    fr = Fraction(v)
+    if fr == 0:
+        return 0.0
+    sign = -1 if fr < 0 else 1
+    fr = abs(fr)
+    e = 0
+    while fr >= 256:
+        fr /= 2
+        e += 1
+    while fr < 128:
+        fr *= 2
+        e -= 1
+    fl = fr.numerator // fr.denominator
+    rem = fr - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    return float(sign * Fraction(fl) * (Fraction(2) ** e))
+
+
+def test_bf16_rounding_is_nearest_even():
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(400) * np.exp(rng.normal(0, 4, 400))).astype(np.float32)
+    # ties: 8-bit significands with the next bit set and nothing below it, both parities
+    ties = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.5 + 2.0 ** -8), 255.5 * 2.0 ** 10, 254.5 * 2.0 ** -20],
+                    dtype=np.float32)
+    got = o.round_to_bf16(np.concatenate([x, ties]))
+    for v, gv in zip(np.concatenate([x, ties]), got):
+        assert float(gv) == _bf16_nearest_even_exact(float(v))
+    assert float(got[-5]) == 1.0 and float(got[-4]) == 1.0 + 2.0 ** -6      # 1 + 2^-8 -> even below, 1 + 3*2^-8 -> even above
+
+
+def test_method_1_on_bf16_operands_against_the_exact_method_1():
+    s, cal, W = _setup(seed=31, d=64, M=9, g=4, bits=4, N=12)
+    codes, _, _ = o.ln_quant(s.x, s.gamma, s.beta, 1e-5, False, cal.perm, cal.cluster_off, cal.inv_s, cal.z, 4)
+    wq, sW, _, zW = o.quantize_weights(W, cal.perm)
+    exact = o.cluster_gemm_dequant(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    xh, wh, Y = o.cluster_gemm_dequant_bf16(codes, wq, cal.cluster_off, cal.s, cal.z, sW, zW)
+    # every operand is the bf16 nearest to its exact value s (q - z) rounded once to fp32
+    sizes = np.diff(cal.cluster_off)
+    sx = np.repeat(cal.s, sizes)
+    zx = np.repeat(cal.z, sizes)
+    for t, j in ((0, 0), (3, 17), (8, 63), (5, 40)):
+        f32 = float(np.float32(float(sx[j]) * (int(codes[t, j]) - int(zx[j]))))
+        assert float(xh[t, j]) == _bf16_nearest_even_exact(f32)
+    for n, j in ((0, 0), (11, 63), (4, 9)):
+        f32 = float(np.float32(float(sW[n]) * (int(wq[n, j]) - int(zW[n]))))
+        assert float(wh[n, j]) == _bf16_nearest_even_exact(f32)
+    # the product of the rounded operands lies within the rounding bound of two bf16 factors of the exact product
+    xe = sx[None, :].astype(np.float64) * (codes.astype(np.float64) - zx[None, :])
+    we = sW[:, None].astype(np.float64) * (wq.astype(np.float64) - zW[:, None])
+    bound = (2.0 ** -8 + 2.0 ** -16) * (np.abs(xe) @ np.abs(we).T)
+    assert np.all(np.abs(Y - exact) <= bound)
+    assert np.abs(Y - exact).max() > 0          # and the rounding is really there
+
+    # scales that are powers of two and small integers: every de-quantized value is a bf16 number, so the
+    # bf16 form is the exact first method
+    sX2 = np.array([0.5, 2.0, 0.125, 1.0], dtype=np.float32)
+    sW2 = (2.0 ** np.arange(-6, 6)).astype(np.float32)
+    xh2, wh2, Y2 = o.cluster_gemm_dequant_bf16(codes, wq, cal.cluster_off, sX2, cal.z, sW2, zW)
+    assert np.abs(codes - np.repeat(cal.z, sizes)[None, :]).max() < 256
+    assert np.array_equal(Y2, o.cluster_gemm_dequant(codes, wq, cal.cluster_off, sX2, cal.z, sW2, zW))
