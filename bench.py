@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, TFLOP/s (the first method of App. A.4, a row beyond the step)
 EPS = 1e-5
 
 
@@ -413,6 +414,46 @@ def main():
             ach = work / (ms * 1e-3) * scale
             next_rows[kname] = dict(ms=round(ms, 5), bound=bound, achieved=round(ach, 1), unit=unit, frac=round(ach / peak, 4))
         del lcw
+
+    # ... and the first method of App. A.4 on the same layer: de-quantize the codes to bf16 (per call), bf16 matrix
+    # cores with fp32 accumulation (weights de-quantized once, offline); judged against the bf16 peak
+    if s_last["lins"][0]["ys"] is not None:
+        cal_l, lin_l = s_last["run_cal"], s_last["lins"][0]
+        d_l, N_l, kp_l = s_last["spec"].d, lin_l["N"], cal_l.k_padded
+        if N_l % 4 == 0 and (N_l + M) * kp_l * 2 < 8e9:
+            fl = lin_l["copies"][0]
+            w_hat = torch.empty((N_l, kp_l), dtype=torch.bfloat16, device="cuda")
+            x_hat = torch.empty((M, kp_l), dtype=torch.bfloat16, device="cuda")
+            rp.rptq_dequant_weights(fl.Wq, N_l, cal_l.cluster_off, fl.sW, fl.zW, w_hat)
+            y1 = lin_l["ys"][0]
+
+            def m1_dequant(i):
+                rp.rptq_dequant_codes(s_last["codes"], M, bits, cal_l.cluster_off, cal_l.s, cal_l.z, x_hat)
+
+            def m1_gemm(i):
+                rp.rptq_gemm_bf16(x_hat, w_hat, M, N_l, kp_l, y1)
+            m1_dequant(0)
+            for kname, kfn, work, peak, unit, scale, bound in (
+                    ("method1_dequant_codes:%s" % lin_l["name"], m1_dequant, M * (d_l * bits / 8.0 + 2.0 * d_l), PEAK_HBM_GBS,
+                     "GB/s", 1e-9, "hbm"),
+                    ("method1_gemm_bf16:%s" % lin_l["name"], m1_gemm, 2.0 * M * N_l * d_l, PEAK_BF16_TFLOPS, "TFLOP/s", 1e-12,
+                     "mfma")):
+                for i in range(3):
+                    kfn(i)
+                torch.cuda.synchronize()
+                ts = []
+                for bi in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(R if M > 32 else 5):
+                        kfn(i)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ts.append(e0.elapsed_time(e1) / (R if M > 32 else 5))
+                ms = robust_mean(ts)
+                ach = work / (ms * 1e-3) * scale
+                next_rows[kname] = dict(ms=round(ms, 5), bound=bound, achieved=round(ach, 1), unit=unit, frac=round(ach / peak, 4))
+            del w_hat, x_hat
 
     # ---- CPU oracle on the host cores (reported baseline) -----------------------------------------
     cpu = None

@@ -217,6 +217,30 @@ int32_t rptq_ln_quant_scatter(const void* x, int64_t M, int32_t d, const float* 
                               const float* inv_s, const int32_t* z, int32_t bits, void* codes_packed,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- the first method of App. A.4 as a measured alternative ------------------------------
+ * "De-quantize, concatenate, multiply in floating point": both operands are turned back into
+ * x_hat = s (x_q - z) (the line under Eq. 1) - the integer difference exact in fp32, one fp32
+ * product, one rounding to bf16 (ties to even) - in the padded cluster-order layout with zeros
+ * at pad positions, and multiplied on the bf16 matrix cores with fp32 accumulation:
+ *   Y[t,o] = sum_j x_hat[t,j] w_hat[o,j].
+ * Kept beside rptq_cluster_gemm (the second method) to measure what the integer form saves.
+ *  rptq_dequant_codes:    codes_packed device (M rows, bits in {3,4,8}); cluster_off,sX,zX host
+ *                         [g+1],[g],[g]; x_hat device out bf16 [M, K_p]
+ *  rptq_dequant_weights:  Wq_packed device (N, K_p) as written by rptq_fold_reorder; sW device
+ *                         fp32 [N], zW device int32 [N]; w_hat device out bf16 [N, K_p]
+ *  rptq_gemm_bf16:        x_hat, w_hat device bf16 [M,K], [N,K] row-major, K a multiple of 64
+ *                         (K_p is), N a multiple of 4; y device out [M,N] row-major, y_dtype
+ *                         RPTQ_DTYPE_BF16 or RPTQ_DTYPE_F32
+ * All three are asynchronous on `stream`, allocate nothing, 16-byte aligned device pointers;
+ * RPTQ_ERR_SHAPE / _RANGE / _ALIGN / _NULL as for the other entry points.
+ */
+int32_t rptq_dequant_codes(const void* codes_packed, int64_t M, int32_t bits, const int32_t* cluster_off, int32_t g,
+                           const float* sX, const int32_t* zX, void* x_hat, void* stream);
+int32_t rptq_dequant_weights(const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g, const float* sW,
+                             const int32_t* zW, void* w_hat, void* stream);
+int32_t rptq_gemm_bf16(const void* x_hat, const void* w_hat, int64_t M, int32_t N, int32_t K, void* y, int32_t y_dtype,
+                       void* stream);
+
 /* ---- online stage 3: cluster-wise integer product (App. A.4, second method) ------
  * Per cluster i the int32 product P_i[t,o] = sum_{c in i} xq[t,c] wq[o,c] runs on int8
  * MFMA; with the zero-point terms of App. A.4 the result is

@@ -39,6 +39,9 @@ from .binding import (  # noqa: F401
     rptq_kv_tables,
     rptq_kv_quant,
     rptq_kv_dequant,
+    rptq_dequant_codes,
+    rptq_dequant_weights,
+    rptq_gemm_bf16,
     rptq_device_info,
     rptq_strerror,
     rptq_version,

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "rptq_cw_scale_bytes", "rptq_cw_cross_bytes", "rptq_cw_rowsum_bytes", "rptq_fold_reorder_cw", "rptq_cluster_rowsums",
     "rptq_cluster_gemm_cw", "rptq_cluster_gemm_partials_cw",
     "rptq_cluster_channels", "rptq_cluster_heads", "rptq_kv_table_bytes", "rptq_kv_tables", "rptq_kv_quant",
-    "rptq_kv_dequant", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
+    "rptq_kv_dequant", "rptq_dequant_codes", "rptq_dequant_weights", "rptq_gemm_bf16", "rptq_device_info", "rptq_strerror", "rptq_last_hip_error", "rptq_version",
 )
 
 _LIB = None
@@ -70,6 +70,9 @@ def load_library():
         "rptq_ln_quant": (i32, [vp, i64, i32, vp, vp, f32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp]),
         "rptq_ln_quant_scatter": (i32, [vp, i64, i32, vp, vp, f32, i32, vp, vp, i32, vp, vp, i32, vp, vp, sz, vp]),
         "rptq_ln_quant_scatter_workspace_bytes": (sz, [i64, i32, i32]),
+        "rptq_dequant_codes": (i32, [vp, i64, i32, vp, i32, vp, vp, vp, vp]),
+        "rptq_dequant_weights": (i32, [vp, i32, vp, i32, vp, vp, vp, vp]),
+        "rptq_gemm_bf16": (i32, [vp, vp, i64, i32, i32, vp, i32, vp]),
         "rptq_cluster_gemm": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, vp]),
         "rptq_cluster_gemm_quant": (i32, [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, i32,
                                           vp, i32, vp, vp, vp, i32, vp, vp, vp, sz, vp]),
@@ -314,6 +317,37 @@ def rptq_ln_quant_scatter(x, M: int, d: int, gamma, beta, eps: float, relu: bool
         int(bool(relu)), _dev(perm_pad, torch.int32), poff, len(off) - 1, pi, pz, bits, _dev(codes_packed),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "rptq_ln_quant_scatter")
+
+
+def rptq_dequant_codes(codes_packed, M: int, bits: int, cluster_off, sX, zX, x_hat, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    sx, psx = _host(sX, np.float32)
+    zx, pzx = _host(zX, np.int32)
+    st = load_library().rptq_dequant_codes(_dev(codes_packed), M, bits, poff, len(off) - 1, psx, pzx,
+                                           _dev(x_hat, torch.bfloat16), _stream(stream))
+    _check(st, "rptq_dequant_codes")
+
+
+def rptq_dequant_weights(Wq_packed, N: int, cluster_off, sW, zW, w_hat, stream=None):
+    import torch
+    off, poff = _host(cluster_off, np.int32)
+    st = load_library().rptq_dequant_weights(_dev(Wq_packed), N, poff, len(off) - 1, _dev(sW, torch.float32),
+                                             _dev(zW, torch.int32), _dev(w_hat, torch.bfloat16), _stream(stream))
+    _check(st, "rptq_dequant_weights")
+
+
+def rptq_gemm_bf16(x_hat, w_hat, M: int, N: int, K: int, y, stream=None):
+    import torch
+    if y.dtype == torch.float32:
+        y_dtype = DTYPE_F32
+    elif y.dtype == torch.bfloat16:
+        y_dtype = DTYPE_BF16
+    else:
+        raise ValueError("y must be bf16 or fp32")
+    st = load_library().rptq_gemm_bf16(_dev(x_hat, torch.bfloat16), _dev(w_hat, torch.bfloat16), M, N, K, _dev(y), y_dtype,
+                                       _stream(stream))
+    _check(st, "rptq_gemm_bf16")
 
 
 def rptq_cluster_gemm(codes_packed, M: int, bits: int, Wq_packed, N: int, cluster_off, sX, sW, zW, colterm,

@@ -11,7 +11,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "librptq.so")
-SOURCES = ["host.cpp", "api.cpp", "calib_minmax.hip", "fold.hip", "ln_quant.hip", "gemm.hip", "kv_cache.hip", "ln_scatter.hip"]
+SOURCES = ["host.cpp", "api.cpp", "calib_minmax.hip", "fold.hip", "ln_quant.hip", "gemm.hip", "kv_cache.hip", "ln_scatter.hip", "method1.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off",

@@ -470,4 +470,39 @@ int32_t rptq_unpack_weights(const void* Wq_packed, int32_t N, const int32_t* clu
   return launch_unpack_weights(Wq_packed, N, geom, out, static_cast<hipStream_t>(stream));
 }
 
+// ---- first method of App. A.4 (comparison variant) ------------------------------------------------
+int32_t rptq_dequant_codes(const void* codes_packed, int64_t M, int32_t bits, const int32_t* cluster_off, int32_t g,
+                           const float* sX, const int32_t* zX, void* x_hat, void* stream) {
+  if (!codes_packed || !sX || !zX || !x_hat) return RPTQ_ERR_NULL;
+  if (int32_t st = check_bits(bits)) return st;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (M < 0) return RPTQ_ERR_SHAPE;
+  for (int i = 0; i < g; ++i) {
+    if (!(std::isfinite(sX[i]) && sX[i] > 0.0f)) return RPTQ_ERR_RANGE;
+    if (zX[i] > kZLimit || zX[i] < -kZLimit) return RPTQ_ERR_RANGE;
+  }
+  if (!aligned16(codes_packed) || !aligned16(x_hat)) return RPTQ_ERR_ALIGN;
+  return launch_dequant_codes(codes_packed, M, geom, bits, sX, zX, x_hat, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_dequant_weights(const void* Wq_packed, int32_t N, const int32_t* cluster_off, int32_t g, const float* sW,
+                             const int32_t* zW, void* w_hat, void* stream) {
+  if (!Wq_packed || !sW || !zW || !w_hat) return RPTQ_ERR_NULL;
+  ClusterGeom geom;
+  if (int32_t st = check_clusters(cluster_off, g, &geom)) return st;
+  if (N < 1) return RPTQ_ERR_SHAPE;
+  if (!aligned16(Wq_packed) || !aligned16(sW) || !aligned16(zW) || !aligned16(w_hat)) return RPTQ_ERR_ALIGN;
+  return launch_dequant_weights(Wq_packed, N, geom, sW, zW, w_hat, static_cast<hipStream_t>(stream));
+}
+
+int32_t rptq_gemm_bf16(const void* x_hat, const void* w_hat, int64_t M, int32_t N, int32_t K, void* y, int32_t y_dtype,
+                       void* stream) {
+  if (!x_hat || !w_hat || !y) return RPTQ_ERR_NULL;
+  if (M < 0 || N < 4 || (N % 4) != 0 || K < 64 || (K % 64) != 0 || K > RPTQ_MAX_K_PADDED) return RPTQ_ERR_SHAPE;
+  if (y_dtype != RPTQ_DTYPE_BF16 && y_dtype != RPTQ_DTYPE_F32) return RPTQ_ERR_SHAPE;
+  if (!aligned16(x_hat) || !aligned16(w_hat) || !aligned16(y)) return RPTQ_ERR_ALIGN;
+  return launch_gemm_bf16(x_hat, w_hat, M, N, K, y, y_dtype == RPTQ_DTYPE_F32, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
+#include "pack_formats.h"
 #include "rptq_internal.h"
 
 namespace rptq {
@@ -23,15 +24,6 @@ __global__ void fold_ln_kernel(const float* gamma, const float* beta, const int3
   const int c = perm_pad[j];
   gamma_pad[j] = c >= 0 ? gamma[c] : 0.0f;
   beta_pad[j] = c >= 0 ? beta[c] : 0.0f;
-}
-
-// Byte offset of the dword holding padded columns 8u..8u+7 of output row o.
-__device__ __host__ __forceinline__ size_t weight_dword_offset(int o, int u, int k_padded) {
-  const int rb = o >> 5, r = o & 31;
-  const int kb = u >> 4, s = (u >> 2) & 3, k8 = u & 3, h = k8 >> 1, v = k8 & 1;
-  // block [rb][kb] of 2 KiB = two halves of 1 KiB (slices 0,1 | 2,3), each: 64 lanes x 16 bytes
-  return ((static_cast<size_t>(rb) * (k_padded / kWBlockCols) + kb) * 2 + (s >> 1)) * 1024 +
-         static_cast<size_t>(h * 32 + r) * 16 + (s & 1) * 8 + v * 4;
 }
 
 struct FoldArgs {

@@ -136,6 +136,13 @@ int32_t launch_ln_scatter(const void* x, int64_t M, int32_t d, const float* gamm
 int32_t launch_unpack_codes(const void* codes, int64_t rows, const ClusterGeom& geom, int32_t bits, int8_t* out,
                             hipStream_t st);
 int32_t launch_unpack_weights(const void* Wq, int32_t N, const ClusterGeom& geom, int8_t* out, hipStream_t st);
+// method1.hip: the first method of App. A.4 (de-quantize to bf16, floating-point product)
+int32_t launch_dequant_codes(const void* codes, int64_t M, const ClusterGeom& geom, int32_t bits, const float* sX,
+                             const int32_t* zX, void* out, hipStream_t st);
+int32_t launch_dequant_weights(const void* Wq, int32_t N, const ClusterGeom& geom, const float* sW, const int32_t* zW,
+                               void* out, hipStream_t st);
+int32_t launch_gemm_bf16(const void* xh, const void* wh, int64_t M, int32_t N, int32_t K, void* y, int32_t y_f32,
+                         hipStream_t st);
 int32_t launch_kv_quant(const void* x, int64_t T, int32_t d, const KvPos* pos, int32_t bits, void* codes, hipStream_t st);
 int32_t launch_kv_dequant(const void* codes, int64_t T, int32_t d, const KvPos* pos, int32_t bits, void* out, hipStream_t st);
 // Per-head clustering (host.cpp), exposed through rptq_cluster_heads.
