@@ -97,15 +97,16 @@ __global__ void __launch_bounds__(256, 2) cluster_gemm_kernel(GemmArgs a, GemmTa
   int lin = blockIdx.x;
   if (total % 8 == 0) lin = (lin & 7) * (total >> 3) + (lin >> 3);
   // The workgroups resident on an XCD at one time (64 with two per compute unit) should share
-  // operands in its L2: they cover 16 row tiles x 4 column tiles (5 MB + 6.7 MB of operands at
-  // K = 12288) rather than 64 row tiles x 1 column tile (20 MB + 1.7 MB).
+  // operands in its L2: blocks of grp_m row tiles x grp_n column tiles (16 x 4 tiles: 5 MB + 6.7 MB of
+  // operands at K = 12288) rather than 64 row tiles x 1 column tile (20 MB + 1.7 MB).
   int tm = lin % tiles_m, tn = lin / tiles_m;
-  if (tiles_m % 16 == 0) {
-    const int group = lin / (4 * tiles_m), rem = lin % (4 * tiles_m);
-    const int wg = (tiles_n - 4 * group) < 4 ? (tiles_n - 4 * group) : 4;      // column tiles of this group
-    const int chunk = rem / (16 * wg), r = rem % (16 * wg);
-    tm = chunk * 16 + r / wg;
-    tn = 4 * group + r % wg;
+  const int GM = a.grp_m, GN = a.grp_n;
+  if (GM > 0) {
+    const int group = lin / (GN * tiles_m), rem = lin % (GN * tiles_m);
+    const int wg = (tiles_n - GN * group) < GN ? (tiles_n - GN * group) : GN;      // column tiles of this group
+    const int chunk = rem / (GM * wg), r = rem % (GM * wg);
+    tm = chunk * GM + r / wg;
+    tn = GN * group + r % wg;
   }
   const int64_t m0 = static_cast<int64_t>(tm) * BM;
   const int n0 = tn * BN;
@@ -688,6 +689,10 @@ static int32_t launch_cfg(const GemmArgs& a, const GemmTab& tab, const GemmQuant
   GemmArgs b = a;
   b.tiles_n = (a.N + BN - 1) / BN;
   b.tiles_m = static_cast<int32_t>((a.M + BM - 1) / BM);
+  // tile order inside an XCD's range: blocks of 32 (16) row tiles x 4 column tiles (measured best of the
+  // shapes from 4 x 16 to 128 x 2 on the 8192 x 49152 x 12288 product, 1 % over 16 x 4, 5 % over 4 x 16)
+  b.grp_m = (b.tiles_m % 32 == 0) ? 32 : ((b.tiles_m % 16 == 0) ? 16 : 0);
+  b.grp_n = 4;
   const dim3 grid(static_cast<unsigned>(b.tiles_n) * static_cast<unsigned>(b.tiles_m));
   hipLaunchKernelGGL(kern, grid, dim3(256), shmem, st, b, tab, qo);
   RPTQ_HIP(hipGetLastError());

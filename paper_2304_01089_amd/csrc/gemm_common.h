@@ -20,6 +20,7 @@ struct GemmArgs {
   int32_t slices;            // K_p / 32
   int32_t used_slices;       // slices up to the end of the last cluster
   int32_t tiles_m, tiles_n;  // output tiles along M and N
+  int32_t grp_m, grp_n;      // tile order: blocks of grp_m row tiles x grp_n column tiles
   const float* sW;
   const int32_t* zW;
   const float* colterm;
