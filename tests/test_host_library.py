@@ -233,3 +233,22 @@ def test_head_clustering_matches_oracle_and_tables_are_validated(lib):
     assert lib.rptq_kv_quant(dummy, 4, d, dummy, 5, dummy, None) == -3
     assert lib.rptq_kv_dequant(dummy, 4, d + 8, dummy, 4, dummy, None) == -2
     assert lib.rptq_kv_quant(None, 4, d, dummy, 4, dummy, None) == -1
+
+
+def test_first_method_entry_points_validate_on_the_host(lib):
+    """rptq_gemm_bf16 / rptq_dequant_* refuse bad shapes and null pointers before any HIP call."""
+    import ctypes
+    fake = ctypes.c_void_p(4096)                       # an aligned non-null address: never dereferenced
+    off = (ctypes.c_int32 * 3)(0, 40, 64)
+    sx = (ctypes.c_float * 2)(0.5, 0.25)
+    zx = (ctypes.c_int32 * 2)(1, -2)
+    assert lib.rptq_gemm_bf16(fake, fake, 8, 8, 200, fake, rp.DTYPE_F32, None) == -2       # K not a multiple of 64
+    assert lib.rptq_gemm_bf16(fake, fake, 8, 6, 256, fake, rp.DTYPE_F32, None) == -2       # N not a multiple of 4
+    assert lib.rptq_gemm_bf16(fake, fake, 8, 8, 256, fake, 7, None) == -2                  # unknown output type
+    assert lib.rptq_gemm_bf16(None, fake, 8, 8, 256, fake, rp.DTYPE_F32, None) == -1
+    assert lib.rptq_dequant_codes(fake, 4, 5, off, 2, sx, zx, fake, None) == -3            # bits
+    assert lib.rptq_dequant_codes(fake, -1, 4, off, 2, sx, zx, fake, None) == -2
+    bad = (ctypes.c_float * 2)(0.5, float("nan"))
+    assert lib.rptq_dequant_codes(fake, 4, 4, off, 2, bad, zx, fake, None) == -6           # scale not finite
+    assert lib.rptq_dequant_weights(fake, 0, off, 2, fake, fake, fake, None) == -2
+    assert lib.rptq_dequant_weights(None, 4, off, 2, fake, fake, fake, None) == -1
