@@ -17,6 +17,7 @@ typedef float f2v __attribute__((ext_vector_type(2)));
 typedef __bf16 b2v __attribute__((ext_vector_type(2)));
 typedef __bf16 b8v __attribute__((ext_vector_type(8)));
 typedef float v16f32 __attribute__((ext_vector_type(16)));
+typedef unsigned u4v __attribute__((ext_vector_type(4)));    // 16 bytes as a plain vector value (a uint4 copy is a memcpy the optimizer leaves in memory)
 
 // s * n for an integer-valued n (exact in fp32), rounded once to fp32 and once to bf16 (ties to even); two at a time
 __device__ __forceinline__ uint32_t dequant_pair(float s0, float n0, float s1, float n1) {
@@ -103,6 +104,24 @@ constexpr int kM1Tile = 128;
 constexpr int kM1Step = 64;                                 // K per step
 constexpr int kM1Operand = kM1Tile * kM1Step * 2;           // bytes of one operand tile of a step
 
+// The MFMAs of one K step: operand fragments from the LDS stage at `stage` (weights, then activations).
+__device__ __forceinline__ void m1_compute(const unsigned char* stage, int wch, int wtok, int frag, v16f32 (&acc)[2][2]) {
+  const unsigned char* wb = stage;
+  const unsigned char* xb = stage + kM1Operand;
+#pragma unroll
+  for (int s = 0; s < kM1Step / 16; ++s) {
+    b8v wf[2], xf[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wf[i] = *reinterpret_cast<const b8v*>(wb + s * 2 * kM1Tile * 16 + (wch + i * 32) * 16 + frag);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) xf[j] = *reinterpret_cast<const b8v*>(xb + s * 2 * kM1Tile * 16 + (wtok + j * 32) * 16 + frag);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+  }
+}
+
 template <bool YF32>
 __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(const uint16_t* xh, const uint16_t* wh, int64_t M, int32_t N,
                                                            int32_t K, void* y, int32_t tiles_m, int32_t tiles_n) {
@@ -128,32 +147,39 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(const uint16_t* xh, c
 
   // this thread's four 16-byte chunks of each operand tile: rows clamped into the tensor (what a
   // clamped row contributes is never stored)
-  const uint4* wsrc[4];
-  const uint4* xsrc[4];
+  const u4v* wsrc[4];
+  const u4v* xsrc[4];
   int lds_off[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int q = tid + 256 * j, row = q >> 3, c = q & 7;    // chunk c = columns 8c .. 8c+7 of the step
     const int64_t wr = (n0 + row) < N ? (n0 + row) : (N - 1);
     const int64_t xr = (m0 + row) < M ? (m0 + row) : (M - 1);
-    wsrc[j] = reinterpret_cast<const uint4*>(wh + wr * K) + c;
-    xsrc[j] = reinterpret_cast<const uint4*>(xh + xr * K) + c;
+    wsrc[j] = reinterpret_cast<const u4v*>(wh + wr * K) + c;
+    xsrc[j] = reinterpret_cast<const u4v*>(xh + xr * K) + c;
     // a 16-column slice s = c >> 1 keeps its two 8-column halves apart: [s][half][row][16 bytes] is the
     // order the MFMA operand is read in (lane = half * 32 + row)
     lds_off[j] = (((c >> 1) * 2 + (c & 1)) * kM1Tile + row) * 16;
   }
-  // (loops written out where they are used: register arrays handed to helper lambdas ended up in scratch memory)
-  uint4 wreg[4], xreg[4];
-#define RPTQ_M1_FETCH(step_)                                 \
-  _Pragma("unroll") for (int j = 0; j < 4; ++j) {            \
-    wreg[j] = wsrc[j][(step_) * (kM1Step / 8)];              \
-    xreg[j] = xsrc[j][(step_) * (kM1Step / 8)];              \
+  // Three register sets hold the operands of the next three steps on their way from memory (one step of
+  // MFMAs is far shorter than a loaded memory latency).  Loops are written out where they are used:
+  // register arrays handed to helper lambdas ended up in scratch memory.
+  struct OperandRegs {
+    u4v w0, w1, w2, w3, x0, x1, x2, x3;
+  } ra, rb, rc;
+#define RPTQ_M1_FETCH(r_, step_)                                                                                  \
+  {                                                                                                               \
+    const int fs_ = ((step_) < steps ? (step_) : (steps - 1)) * (kM1Step / 8); /* past the end: the last step again */ \
+    r_.w0 = wsrc[0][fs_]; r_.x0 = xsrc[0][fs_]; r_.w1 = wsrc[1][fs_]; r_.x1 = xsrc[1][fs_];                         \
+    r_.w2 = wsrc[2][fs_]; r_.x2 = xsrc[2][fs_]; r_.w3 = wsrc[3][fs_]; r_.x3 = xsrc[3][fs_];                         \
   }
-#define RPTQ_M1_STASH(stage_)                                                             \
-  _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-    unsigned char* base_ = smem + (stage_) * 2 * kM1Operand;                              \
-    *reinterpret_cast<uint4*>(base_ + lds_off[j]) = wreg[j];                              \
-    *reinterpret_cast<uint4*>(base_ + kM1Operand + lds_off[j]) = xreg[j];                 \
+#define RPTQ_M1_STASH(r_, stage_)                                                                                 \
+  {                                                                                                               \
+    unsigned char* base_ = smem + (stage_) * 2 * kM1Operand;                                                      \
+    *reinterpret_cast<u4v*>(base_ + lds_off[0]) = r_.w0; *reinterpret_cast<u4v*>(base_ + kM1Operand + lds_off[0]) = r_.x0; \
+    *reinterpret_cast<u4v*>(base_ + lds_off[1]) = r_.w1; *reinterpret_cast<u4v*>(base_ + kM1Operand + lds_off[1]) = r_.x1; \
+    *reinterpret_cast<u4v*>(base_ + lds_off[2]) = r_.w2; *reinterpret_cast<u4v*>(base_ + kM1Operand + lds_off[2]) = r_.x2; \
+    *reinterpret_cast<u4v*>(base_ + lds_off[3]) = r_.w3; *reinterpret_cast<u4v*>(base_ + kM1Operand + lds_off[3]) = r_.x3; \
   }
 
   v16f32 acc[2][2];
@@ -167,30 +193,31 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(const uint16_t* xh, c
   const int wch = (wave & 1) * 64, wtok = (wave >> 1) * 64;    // this wave's channels and tokens inside the tile
   const int frag = ((lane >> 5) * kM1Tile + (lane & 31)) * 16;
 
-  RPTQ_M1_FETCH(0)
-  RPTQ_M1_STASH(0)
-  __syncthreads();
-  for (int step = 0; step < steps; ++step) {
-    const int p = step & 1;
-    const int nstep = (step + 1) < steps ? (step + 1) : step;  // (the last step re-reads its own operands: never used)
-    RPTQ_M1_FETCH(nstep)
-    const unsigned char* wb = smem + p * 2 * kM1Operand;
-    const unsigned char* xb = wb + kM1Operand;
-#pragma unroll
-    for (int s = 0; s < kM1Step / 16; ++s) {
-      b8v wf[2], xf[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) wf[i] = *reinterpret_cast<const b8v*>(wb + s * 2 * kM1Tile * 16 + (wch + i * 32) * 16 + frag);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) xf[j] = *reinterpret_cast<const b8v*>(xb + s * 2 * kM1Tile * 16 + (wtok + j * 32) * 16 + frag);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
-    }
-    RPTQ_M1_STASH(p ^ 1)
-    __syncthreads();
+  // one step: the MFMAs of step k from LDS stage k & 1; then the registers that hold step k + 1 go to the other
+  // stage and are refilled with step k + 4
+#define RPTQ_M1_STEP(k_, set_)               \
+  {                                          \
+    m1_compute(smem + ((k_) & 1) * 2 * kM1Operand, wch, wtok, frag, acc); \
+    RPTQ_M1_STASH(set_, ((k_) & 1) ^ 1)      \
+    RPTQ_M1_FETCH(set_, (k_) + 4)            \
+    __syncthreads();                         \
   }
+
+  RPTQ_M1_FETCH(ra, 0)
+  RPTQ_M1_STASH(ra, 0)
+  RPTQ_M1_FETCH(rb, 1)                        // step j travels in set j % 3 (ra, rb, rc)
+  RPTQ_M1_FETCH(rc, 2)
+  RPTQ_M1_FETCH(ra, 3)
+  __syncthreads();
+  int step = 0;
+  for (; step + 2 < steps; step += 3) {
+    RPTQ_M1_STEP(step, rb)
+    RPTQ_M1_STEP(step + 1, rc)
+    RPTQ_M1_STEP(step + 2, ra)
+  }
+  if (step < steps) RPTQ_M1_STEP(step, rb)
+  if (step + 1 < steps) RPTQ_M1_STEP(step + 1, rc)
+#undef RPTQ_M1_STEP
 #undef RPTQ_M1_FETCH
 #undef RPTQ_M1_STASH
 
