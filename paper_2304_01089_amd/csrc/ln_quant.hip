@@ -20,6 +20,10 @@
 
 namespace rptq {
 
+// 16 bytes as a plain vector value (copies of the runtime's uint4 struct are memory copies, which can keep
+// register arrays in scratch memory)
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+
 struct LnQuantArgs {
   const uint4* x;          // bf16 [M, d], 8 values per uint4
   int64_t M;
@@ -172,11 +176,11 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   // about 3 TB/s: one row of 24 KB per 2 us of loaded-memory latency).
   // (with four chunks per thread a second set does not fit the 128 registers: one row in flight)
   constexpr bool kDeep = NCH <= 2;
-  uint4 nxa[NCH], nxb[kDeep ? NCH : 1];
-  auto fetch_row = [&](int k, uint4* dst) {          // k-th row of this workgroup; past the end: a valid row again
+  u4v nxa[NCH], nxb[kDeep ? NCH : 1];
+  auto fetch_row = [&](int k, u4v* dst) {          // k-th row of this workgroup; past the end: a valid row again
     int64_t row = row0 + k * stride;
     if (row >= a.M) row = a.M - 1;
-    const uint4* p = a.x + row * a.chunks;
+    const u4v* p = reinterpret_cast<const u4v*>(a.x + row * a.chunks);
 #pragma unroll
     for (int c = 0; c < NCH; ++c) dst[c] = p[ch_idx[c]];
   };
@@ -252,14 +256,14 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
   }
 
   // registers -> row buffer, exact fp64 sums of this thread's elements -> partials
-  auto stage_row = [&](const uint4* regs, unsigned char* rowbuf, int pb) {
+  auto stage_row = [&](const u4v* regs, unsigned char* rowbuf, int pb) {
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      uint4 v = regs[c];
-      *reinterpret_cast<uint4*>(rowbuf + ch_lds[c]) = v;
+      u4v v = regs[c];
+      *reinterpret_cast<u4v*>(rowbuf + ch_lds[c]) = v;
       if (LN) {
-        if (!ch_ok[c]) v = make_uint4(0u, 0u, 0u, 0u);       // surplus lane: contributes nothing
+        if (!ch_ok[c]) v = u4v{0u, 0u, 0u, 0u};              // surplus lane: contributes nothing
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -298,7 +302,7 @@ __global__ void __launch_bounds__(1024) ln_quant_kernel(LnQuantArgs a, ClusterGe
     for (int e = 0; e < (FIXED ? UC : 1); ++e) hreg[n][e] = 0u;
 
   // bc_tag: the row buffer that holds row i when it is known at compile time (FIXED), else -1
-  auto row_iter = [&](int i, uint4* regs, auto bc_tag) {
+  auto row_iter = [&](int i, u4v* regs, auto bc_tag) {
     constexpr int BC = decltype(bc_tag)::value;
     const int cur_off = BC >= 0 ? BC * kFixedStride : b_cur;
     const int next_off = BC >= 0 ? ((BC + 1) % 3) * kFixedStride : b_next;
